@@ -1,0 +1,158 @@
+/*
+ * bcq.h -- C ABI of the MI355X (gfx950) binary-coding matrix-vector library.
+ *
+ * The operation is the inference form of GPTQT (arXiv 2407.02891): a linear
+ * layer whose weight is stored as q bit-planes of signs with per-group scales
+ * and an optional per-group offset (paper Eq. 3, dequantisation line, and
+ * Eq. 11, the fused form):
+ *
+ *     W[m][k] = sum_{i<q} alpha[m][k/group][i] * s_i[m][k]  (+ offset[m][k/group])
+ *     y[m]    = sum_k W[m][k] * x[k]                        s_i in {-1,+1}
+ *
+ * evaluated directly on the planes, never materialising W (Sec. II-D, last
+ * paragraph; Sec. III "Speed up of GPTQT").  Activations and outputs are IEEE
+ * binary16 (the paper keeps activations at fp16); accumulation is fp32; the
+ * result is rounded to binary16 to nearest-even.
+ *
+ * Conventions for every entry point
+ *   - plain C types only; a hipStream_t is passed as void* (NULL = the null
+ *     stream); every pointer marked DEVICE must be device memory of the
+ *     current HIP device, every pointer marked HOST is ordinary host memory;
+ *   - the caller owns every buffer; the library never allocates, frees or
+ *     synchronises; work is enqueued on the given stream and the call returns;
+ *   - all argument checks happen on the host before any launch; a failed
+ *     check launches nothing and returns a status other than BCQ_OK;
+ *   - binary16 values travel as uint16_t bit patterns.
+ */
+#ifndef BCQ_H
+#define BCQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    BCQ_OK = 0,
+    BCQ_ERR_INVALID_ARG = 1, /* NULL pointer, bad size, misalignment, bad batch     */
+    BCQ_ERR_UNSUPPORTED = 2, /* well-formed request outside what the kernels cover  */
+    BCQ_ERR_WORKSPACE = 3,   /* workspace missing where bcq_workspace_bytes() > 0   */
+    BCQ_ERR_HIP = 4          /* the HIP runtime reported an error at launch         */
+} bcq_status;
+
+/* Version of the opaque packed layout written by bcq_pack. */
+#define BCQ_LAYOUT_VERSION 1
+
+/* Largest batch bcq_gemm_skinny accepts. */
+#define BCQ_MAX_BATCH 16
+
+/*
+ * Problem descriptor (HOST, plain data, filled by the caller).
+ *   M, N        out rows, in columns; N must be a multiple of 32 and at most
+ *               523776 (larger N is BCQ_ERR_UNSUPPORTED)
+ *   q           number of sign planes, 1..4 (the paper uses 2 and 3)
+ *   group       columns sharing one alpha per plane (and one offset); must
+ *               divide N and be a multiple of 128 or N itself (any N).
+ *               group == N gives the paper's row-wise parameters (Sec. II-A:
+ *               quantisation parameters are fixed per row).  Other multiples
+ *               of 32 are well-formed but BCQ_ERR_UNSUPPORTED.
+ *   has_offset  1 if the fused offset term of Eq. 11, (2^n-1)/2*S + qbias, is
+ *               present, else 0
+ *   layout_version  set by bcq_pack; bcq_gemv / bcq_gemm_skinny / bcq_unpack
+ *               refuse a descriptor whose value is not BCQ_LAYOUT_VERSION
+ */
+typedef struct bcq_desc {
+    int32_t M, N;
+    int32_t q;
+    int32_t group;
+    int32_t has_offset;
+    int32_t layout_version;
+} bcq_desc;
+
+/* Size in bytes of the opaque packed weight blob for this descriptor
+ * (0 if the descriptor is invalid).  HOST-only computation. */
+size_t bcq_packed_bytes(const bcq_desc *desc);
+
+/* Size in bytes of the workspace bcq_gemv (batch = 1) or bcq_gemm_skinny needs
+ * (0 if the descriptor or batch is invalid, or if N <= 512, where no split
+ * over columns happens).  It holds one 64-bit split-K accumulator per row and
+ * batch column.  HOST-only computation. */
+size_t bcq_workspace_bytes(const bcq_desc *desc, int32_t batch);
+
+/*
+ * Zero a workspace.  Required once before its first use; bcq_gemv and
+ * bcq_gemm_skinny leave every accumulator zero again when they finish, so one
+ * workspace can serve any sequence of calls on ONE stream (calls sharing a
+ * workspace must not overlap in time).  Uses a fill kernel, not a memset node,
+ * so it may be captured into a graph.
+ *   workspace DEVICE, 16-byte aligned; bytes a multiple of 4.
+ */
+bcq_status bcq_workspace_init(void *workspace, size_t bytes, void *stream);
+
+/*
+ * Integer weights + scales -> packed bit-planes (Eq. 11 operands).
+ *   codes  DEVICE [M][N] uint8: bit i of codes[m*N+k] is the sign of plane i
+ *          for weight (m,k): 1 means +1, 0 means -1 (the paper leaves the
+ *          encoding open); bits >= q are ignored
+ *   alpha  DEVICE [M][N/group][q] binary16
+ *   offset DEVICE [M][N/group] binary16, or NULL iff desc->has_offset == 0
+ *   packed DEVICE, bcq_packed_bytes(desc) bytes, 256-byte aligned; opaque
+ * Sets desc->layout_version.  Offline step, not part of the timed path.
+ */
+bcq_status bcq_pack(bcq_desc *desc, const uint8_t *codes, const uint16_t *alpha,
+                    const uint16_t *offset, void *packed, void *stream);
+
+/* Inverse of bcq_pack (for tests): any of codes / alpha / offset may be NULL
+ * to skip that output.  All DEVICE. */
+bcq_status bcq_unpack(const bcq_desc *desc, const void *packed, uint8_t *codes,
+                      uint16_t *alpha, uint16_t *offset, void *stream);
+
+/*
+ * y[M] = W_q x[N]  (batch 1; paper Eq. 11 applied to one activation vector).
+ *   packed    DEVICE, written by bcq_pack for the same descriptor
+ *   x         DEVICE [N] binary16, 16-byte aligned
+ *   y         DEVICE [M] binary16, 2-byte aligned
+ *   workspace DEVICE, bcq_workspace_bytes(desc, 1) bytes, 16-byte aligned,
+ *             initialised once with bcq_workspace_init; may be NULL only if
+ *             that size is 0
+ */
+bcq_status bcq_gemv(const bcq_desc *desc, const void *packed, const uint16_t *x,
+                    uint16_t *y, void *workspace, void *stream);
+
+/*
+ * Y[j][m] = sum_k W_q[m][k] X[j][k],  1 <= batch <= BCQ_MAX_BATCH.
+ *   X   DEVICE, row j starts at X + j*ldx (elements), ldx >= N, ldx % 8 == 0
+ *   Y   DEVICE, row j starts at Y + j*ldy (elements), ldy >= M
+ *   workspace as for bcq_gemv with bcq_workspace_bytes(desc, batch)
+ */
+bcq_status bcq_gemm_skinny(const bcq_desc *desc, const void *packed,
+                           const uint16_t *X, int32_t ldx, uint16_t *Y,
+                           int32_t ldy, int32_t batch, void *workspace,
+                           void *stream);
+
+/*
+ * Streaming-read probe: reads `bytes` (a multiple of 16) of DEVICE memory with
+ * the same 128-bit coalesced loads and launch shape the GEMV uses and writes a
+ * 4-byte checksum per workgroup to `sink` (DEVICE, at least
+ * bcq_read_probe_sink_bytes() bytes).  It measures the read bandwidth the
+ * chip can reach, the ceiling against which the GEMV's rate is reported.
+ */
+size_t bcq_read_probe_sink_bytes(void);
+bcq_status bcq_read_probe(const void *buf, size_t bytes, void *sink, void *stream);
+
+/*
+ * Launch-shape overrides for tuning runs (HOST state, process-wide, not
+ * thread-safe).  name: "row_split" (workgroups per column slice, 0 = auto).
+ * Unknown names return BCQ_ERR_INVALID_ARG.
+ */
+bcq_status bcq_set_option(const char *name, int32_t value);
+
+/* Static, NUL-terminated description of a status code. */
+const char *bcq_status_string(bcq_status status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BCQ_H */

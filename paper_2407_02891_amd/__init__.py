@@ -1,0 +1,8 @@
+"""MI355X-native binary-coding GEMV (inference path of GPTQT, arXiv 2407.02891).
+
+Thin Python binding over the C ABI in include/bcq.h; see `binding`.
+"""
+from .binding import (  # noqa: F401
+    BcqError, Desc, PackedLayer, gemm_skinny, gemv, lib, pack, packed_bytes,
+    read_probe, set_option, status_string, unpack, workspace_bytes, workspace_init,
+)

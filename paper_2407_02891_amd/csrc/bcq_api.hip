@@ -1,0 +1,157 @@
+// extern "C" entry points of libbcq: argument validation (host only, before any
+// launch) and dispatch to the kernels.  See include/bcq.h for the contract.
+#include <string.h>
+
+#include "bcq_internal.h"
+
+using namespace bcq;
+
+namespace {
+
+int g_row_split = 0;  // 0 = automatic
+
+bool desc_ok(const bcq_desc *d, bcq_status *why)
+{
+    *why = BCQ_ERR_INVALID_ARG;
+    if (!d) return false;
+    if (d->M <= 0 || d->N <= 0 || d->N % 32 != 0) return false;
+    if (d->q < 1 || d->group <= 0 || d->group % 32 != 0 || d->N % d->group != 0) return false;
+    if (d->has_offset != 0 && d->has_offset != 1) return false;
+    *why = BCQ_ERR_UNSUPPORTED;
+    if (d->q > kMaxQ) return false;
+    const bool one_scale_per_block = d->group % 128 == 0 || d->group == d->N;
+    if (!(one_scale_per_block || d->group == 32 || d->group == 64)) return false;
+    if (!one_scale_per_block) return false;  // groups of 32/64: laid out by bcq_pack, not yet computed by the GEMV
+    if (((long long)d->N + kTileCols - 1) / kTileCols > kMaxSlices) return false;  // split-K arrival count is 10 bits
+    // blob offsets are size_t; tile counts must fit int
+    if ((long long)d->M + kTileRows > 0x7fffffffLL || (long long)d->N + kTileCols > 0x7fffffffLL) return false;
+    *why = BCQ_OK;
+    return true;
+}
+
+inline Geom geom_of(const bcq_desc *d) { return make_geom(d->M, d->N, d->q, d->group, d->has_offset); }
+
+inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+size_t workspace_bytes(const Geom &g, int batch)
+{
+    return ws_bytes(g, batch);
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t bcq_packed_bytes(const bcq_desc *desc)
+{
+    bcq_status why;
+    if (!desc_ok(desc, &why)) return 0;
+    Geom g = geom_of(desc);
+    return (size_t)g.nslice * g.ntile * g.tile_bytes;
+}
+
+size_t bcq_workspace_bytes(const bcq_desc *desc, int32_t batch)
+{
+    bcq_status why;
+    if (!desc_ok(desc, &why) || batch < 1 || batch > BCQ_MAX_BATCH) return 0;
+    return workspace_bytes(geom_of(desc), batch);
+}
+
+bcq_status bcq_workspace_init(void *workspace, size_t bytes, void *stream)
+{
+    if (bytes == 0) return BCQ_OK;
+    if (!workspace || !aligned(workspace, 16) || bytes % 4 != 0) return BCQ_ERR_INVALID_ARG;
+    return launch_fill_zero(workspace, bytes, static_cast<hipStream_t>(stream)) == hipSuccess ? BCQ_OK
+                                                                                             : BCQ_ERR_HIP;
+}
+
+bcq_status bcq_pack(bcq_desc *desc, const uint8_t *codes, const uint16_t *alpha, const uint16_t *offset,
+                    void *packed, void *stream)
+{
+    bcq_status why;
+    if (!desc_ok(desc, &why)) return why;
+    if (!codes || !alpha || !packed) return BCQ_ERR_INVALID_ARG;
+    if ((desc->has_offset != 0) != (offset != nullptr)) return BCQ_ERR_INVALID_ARG;
+    if (!aligned(packed, 256) || !aligned(alpha, 2) || (offset && !aligned(offset, 2))) return BCQ_ERR_INVALID_ARG;
+    if (launch_pack(geom_of(desc), codes, alpha, offset, packed, static_cast<hipStream_t>(stream)) != hipSuccess)
+        return BCQ_ERR_HIP;
+    desc->layout_version = BCQ_LAYOUT_VERSION;
+    return BCQ_OK;
+}
+
+bcq_status bcq_unpack(const bcq_desc *desc, const void *packed, uint8_t *codes, uint16_t *alpha,
+                      uint16_t *offset, void *stream)
+{
+    bcq_status why;
+    if (!desc_ok(desc, &why)) return why;
+    if (desc->layout_version != BCQ_LAYOUT_VERSION) return BCQ_ERR_INVALID_ARG;
+    if (!packed || !aligned(packed, 256)) return BCQ_ERR_INVALID_ARG;
+    if (offset && !desc->has_offset) return BCQ_ERR_INVALID_ARG;
+    if ((alpha && !aligned(alpha, 2)) || (offset && !aligned(offset, 2))) return BCQ_ERR_INVALID_ARG;
+    if (launch_unpack(geom_of(desc), packed, codes, alpha, offset, static_cast<hipStream_t>(stream)) != hipSuccess)
+        return BCQ_ERR_HIP;
+    return BCQ_OK;
+}
+
+bcq_status bcq_gemm_skinny(const bcq_desc *desc, const void *packed, const uint16_t *X, int32_t ldx,
+                           uint16_t *Y, int32_t ldy, int32_t batch, void *workspace, void *stream)
+{
+    bcq_status why;
+    if (!desc_ok(desc, &why)) return why;
+    if (desc->layout_version != BCQ_LAYOUT_VERSION) return BCQ_ERR_INVALID_ARG;
+    if (batch < 1 || batch > BCQ_MAX_BATCH) return BCQ_ERR_INVALID_ARG;
+    if (!packed || !X || !Y) return BCQ_ERR_INVALID_ARG;
+    if (!aligned(packed, 256) || !aligned(X, 16) || !aligned(Y, 2)) return BCQ_ERR_INVALID_ARG;
+    if (ldx < desc->N || ldy < desc->M || ldx % 8 != 0) return BCQ_ERR_INVALID_ARG;
+    Geom g = geom_of(desc);
+    if (workspace_bytes(g, batch) > 0 && (!workspace || !aligned(workspace, 16))) return BCQ_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    // One pass of the table kernel per activation row (launches on one stream
+    // run in order, so they can share the workspace).
+    for (int j = 0; j < batch; ++j) {
+        if (launch_gemv(g, packed, X + (size_t)j * ldx, Y + (size_t)j * ldy, workspace, g_row_split, s) != hipSuccess)
+            return BCQ_ERR_HIP;
+    }
+    return BCQ_OK;
+}
+
+bcq_status bcq_gemv(const bcq_desc *desc, const void *packed, const uint16_t *x, uint16_t *y, void *workspace,
+                    void *stream)
+{
+    if (!desc) return BCQ_ERR_INVALID_ARG;
+    return bcq_gemm_skinny(desc, packed, x, desc->N, y, desc->M, 1, workspace, stream);
+}
+
+size_t bcq_read_probe_sink_bytes(void) { return (size_t)kProbeBlocks * 4; }
+
+bcq_status bcq_read_probe(const void *buf, size_t bytes, void *sink, void *stream)
+{
+    if (!buf || !sink || bytes == 0 || bytes % 16 != 0 || !aligned(buf, 16) || !aligned(sink, 4))
+        return BCQ_ERR_INVALID_ARG;
+    return launch_read_probe(buf, bytes, sink, static_cast<hipStream_t>(stream)) == hipSuccess ? BCQ_OK
+                                                                                              : BCQ_ERR_HIP;
+}
+
+bcq_status bcq_set_option(const char *name, int32_t value)
+{
+    if (!name || value < 0) return BCQ_ERR_INVALID_ARG;
+    if (strcmp(name, "row_split") == 0) {
+        g_row_split = value;
+        return BCQ_OK;
+    }
+    return BCQ_ERR_INVALID_ARG;
+}
+
+const char *bcq_status_string(bcq_status status)
+{
+    switch (status) {
+        case BCQ_OK: return "ok";
+        case BCQ_ERR_INVALID_ARG: return "invalid argument";
+        case BCQ_ERR_UNSUPPORTED: return "unsupported configuration";
+        case BCQ_ERR_WORKSPACE: return "workspace missing or misaligned";
+        case BCQ_ERR_HIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+}  // extern "C"

@@ -1,0 +1,377 @@
+// Batch-1 binary-coding GEMV for gfx950 (paper Eq. 11 evaluated on the planes).
+//
+//   y[m] = sum_blocks sum_i alpha_i[m,blk] * S_i[m,blk]  (+ z[m,blk] * X[blk])
+//   S_i[m,blk] = sum_{k in blk} s_i[m,k] x[k],   X[blk] = sum_{k in blk} x[k]
+//
+// HBM-bound by design: every plane word and scale is read once with 128-bit
+// coalesced loads; the sign sums cost one LDS read and two VALU operations per
+// 8 weights instead of one VALU operation per weight:
+//
+//  * A workgroup owns one column slice of 512 activations.  It first builds, in
+//    LDS, one 256-entry fp32 table per 8 consecutive activations ("chunk"):
+//    table[c][p] = sum_{b<8} (bit b of p ? +x : -x)[8c+b]  (the sign-sum lookup
+//    idea of the LUT-GEMM kernel the paper cites, re-laid out for a 64-bank-free
+//    access pattern): entry p of chunk c sits at byte p*256 + 4*c, so a chunk
+//    lives in one LDS bank and the 64 chunks of the slice cover 64 dword columns.
+//  * Each lane owns one (row, 128-column block, plane) at a time: 16 bytes of
+//    sign bits = 16 table indices.  The packed blob stores a lane's 16 bytes
+//    rotated by (row mod 16), so at lookup step j the 16 lanes that share a
+//    block read 16 different chunks, and the four blocks of a wave are disjoint:
+//    every ds_read_b32 of the wave is bank-conflict free.
+//  * The LDS byte address (index*256 + 4*chunk) is assembled by one v_perm_b32
+//    from a byte of the plane word and a byte of a per-lane constant.
+//  * Lanes accumulate privately in fp32; the four block owners of a row are
+//    summed with two cross-lane steps once per 32-row tile.
+//  * Column slices are combined with ONE device-scope 64-bit integer atomic per
+//    row and slice: the fp32 partial is converted to fixed point (2^-34 units,
+//    54 bits, two's complement, wrapping) and added, together with an arrival
+//    count in the low 10 bits, to the row's accumulator word in the workspace.
+//    Integer addition commutes exactly, so the sum does not depend on arrival
+//    order; the lane whose atomic returns the last arrival count owns the final
+//    sum (returned value + own term), rounds it to binary16, stores y and
+//    re-arms the word with zero.  No partial arrays, no fences, no second pass.
+#include "bcq_internal.h"
+
+namespace bcq {
+
+struct GemvParams {
+    const uint8_t *blob;
+    const uint16_t *x;
+    uint16_t *y;
+    unsigned long long *accum;  // [Mp] fixed-point row accumulators (value << 10 | arrivals)
+    int M, N, Mp;
+    int ntile, nslice;
+    int waves_per_slice;  // row_split * NW
+    unsigned tile_bytes;
+};
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));  // one 128-bit load
+
+__device__ __forceinline__ float half_bits_to_float(uint32_t bits16)
+{
+    return static_cast<float>(__builtin_bit_cast(_Float16, static_cast<uint16_t>(bits16)));
+}
+
+__device__ __forceinline__ uint16_t float_to_half_bits(float v)
+{
+    return __builtin_bit_cast(uint16_t, static_cast<_Float16>(v));  // round to nearest even
+}
+
+// One table lookup: byte `n` of plane word `w` is the index, byte `n` of `rv`
+// is 4*chunk; the LDS byte address is index*256 + 4*chunk.
+template <int n>
+__device__ __forceinline__ float lookup(const float *lut, uint32_t w, uint32_t rv)
+{
+    constexpr uint32_t sel = 0x0c0c0000u | ((4u + n) << 8) | (uint32_t)n;
+    uint32_t addr = __builtin_amdgcn_perm(w, rv, sel);
+    return *reinterpret_cast<const float *>(reinterpret_cast<const char *>(lut) + addr);
+}
+
+__device__ __forceinline__ float sign_sum16(const float *lut, const u32x4 &p, const uint32_t (&rv)[4])
+{
+    float s = lookup<0>(lut, p.x, rv[0]);
+    s += lookup<1>(lut, p.x, rv[0]);
+    s += lookup<2>(lut, p.x, rv[0]);
+    s += lookup<3>(lut, p.x, rv[0]);
+    s += lookup<0>(lut, p.y, rv[1]);
+    s += lookup<1>(lut, p.y, rv[1]);
+    s += lookup<2>(lut, p.y, rv[1]);
+    s += lookup<3>(lut, p.y, rv[1]);
+    s += lookup<0>(lut, p.z, rv[2]);
+    s += lookup<1>(lut, p.z, rv[2]);
+    s += lookup<2>(lut, p.z, rv[2]);
+    s += lookup<3>(lut, p.z, rv[2]);
+    s += lookup<0>(lut, p.w, rv[3]);
+    s += lookup<1>(lut, p.w, rv[3]);
+    s += lookup<2>(lut, p.w, rv[3]);
+    s += lookup<3>(lut, p.w, rv[3]);
+    return s;
+}
+
+template <int Q, int Z>
+struct TileRegs {
+    u32x4 planes[2][Q];
+    uint32_t scales[Q + Z];  // binary16 pairs: [t][c] flattened, 2*(Q+Z) halves
+};
+
+template <int Q, int Z>
+__device__ __forceinline__ void load_tile(TileRegs<Q, Z> &r, const uint8_t *tile, int lane)
+{
+    const u32x4 *pp = reinterpret_cast<const u32x4 *>(tile) + lane;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int i = 0; i < Q; ++i) r.planes[t][i] = __builtin_nontemporal_load(pp + (t * Q + i) * 64);
+    const uint32_t *sp = reinterpret_cast<const uint32_t *>(tile + 2u * Q * 1024u) + lane * (Q + Z);
+#pragma unroll
+    for (int c = 0; c < Q + Z; ++c) r.scales[c] = __builtin_nontemporal_load(sp + c);
+}
+
+template <int Q, int Z>
+__device__ __forceinline__ float scale_of(const TileRegs<Q, Z> &r, int t, int c)
+{
+    int e = t * (Q + Z) + c;  // half index
+    uint32_t pair = r.scales[e >> 1];
+    return half_bits_to_float((e & 1) ? (pair >> 16) : (pair & 0xffffu));
+}
+
+// Split-K accumulator word: bits 63..10 = sum of the slices' partials in units of
+// 2^-34 (two's complement, wraps modulo 2^54), bits 9..0 = number of slices that
+// have arrived.  A slice adds (fixed << 10) + 1.
+constexpr int kCountBits = 10;
+constexpr double kFixedScale = 17179869184.0;  // 2^34
+
+__device__ __forceinline__ unsigned long long encode_partial(float v)
+{
+    // keep the conversion in range; magnitudes this large cannot end in a finite binary16
+    v = fminf(fmaxf(v, -536870848.0f), 536870848.0f);  // |v| < 2^29
+    long long fixed = __double2ll_rn(static_cast<double>(v) * kFixedScale);  // exact product
+    return (static_cast<unsigned long long>(fixed) << kCountBits) + 1ull;
+}
+
+// Completes one row: `total` is the accumulator word after this slice's add.  The
+// slice that arrives last converts the sum to binary16, stores it and zeroes the
+// word for the next call.
+__device__ __forceinline__ void complete_row(const GemvParams &p, int row, unsigned long long total)
+{
+    if ((total & ((1u << kCountBits) - 1u)) == (unsigned)p.nslice) {
+        const long long fixed = static_cast<long long>(total) >> kCountBits;
+        const float v = static_cast<float>(static_cast<double>(fixed) * (1.0 / kFixedScale));
+        if (row < p.M) p.y[row] = float_to_half_bits(v);
+        __hip_atomic_store(p.accum + row, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
+template <int Q, int Z, int NW>
+__global__ __launch_bounds__(NW * 64) void bcq_gemv_kernel(GemvParams p)
+{
+    __shared__ float lut[256 * 64];  // 64 KB: entry idx of chunk c at lut[idx*64 + c]
+
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int slice = blockIdx.x % p.nslice;
+    const int part = blockIdx.x / p.nslice;
+
+    // Row tiles of this wave: an even split of the ntile tiles over all waves of the slice.
+    const int gw = part * NW + wave;
+    const int t_begin = (int)(((long long)gw * p.ntile) / p.waves_per_slice);
+    const int t_end = (int)(((long long)(gw + 1) * p.ntile) / p.waves_per_slice);
+    const uint8_t *tile_ptr = p.blob + ((size_t)slice * p.ntile + t_begin) * p.tile_bytes;
+
+    // Start the first tile's loads before building the tables.
+    TileRegs<Q, Z> cur;
+    if (t_begin < t_end) load_tile<Q, Z>(cur, tile_ptr, lane);
+
+    // ---- sign-sum tables for the 512 activations of this slice ----------------
+    {
+        const int col0 = slice * kTileCols + kChunkCols * lane;  // lane = chunk
+        u32x4 xr = {0u, 0u, 0u, 0u};
+        if (col0 < p.N) xr = *reinterpret_cast<const u32x4 *>(p.x + col0);
+        float xv[8];
+        xv[0] = half_bits_to_float(xr.x & 0xffffu); xv[1] = half_bits_to_float(xr.x >> 16);
+        xv[2] = half_bits_to_float(xr.y & 0xffffu); xv[3] = half_bits_to_float(xr.y >> 16);
+        xv[4] = half_bits_to_float(xr.z & 0xffffu); xv[5] = half_bits_to_float(xr.z >> 16);
+        xv[6] = half_bits_to_float(xr.w & 0xffffu); xv[7] = half_bits_to_float(xr.w >> 16);
+
+        constexpr int IPW = 256 / NW;               // indices built by one wave
+        constexpr int LB = (IPW == 64) ? 6 : (IPW == 32) ? 5 : (IPW == 128) ? 7 : 4;
+        static_assert((1 << LB) == IPW, "NW must be 2, 4, 8 or 16");
+        // bits >= LB of the index are fixed per wave
+        float hi = 0.0f;
+#pragma unroll
+        for (int b = LB; b < 8; ++b) hi += ((wave >> (b - LB)) & 1) ? xv[b] : -xv[b];
+        float lo[8];
+#pragma unroll
+        for (int a = 0; a < 8; ++a)
+            lo[a] = ((a & 1) ? xv[0] : -xv[0]) + ((a & 2) ? xv[1] : -xv[1]) + ((a & 4) ? xv[2] : -xv[2]);
+#pragma unroll
+        for (int m = 0; m < IPW / 8; ++m) {
+            float mid = hi;
+#pragma unroll
+            for (int b = 3; b < LB; ++b) mid += ((m >> (b - 3)) & 1) ? xv[b] : -xv[b];
+#pragma unroll
+            for (int a = 0; a < 8; ++a) lut[(wave * IPW + m * 8 + a) * 64 + lane] = lo[a] + mid;
+        }
+    }
+    __syncthreads();
+
+    // ---- per-lane constants ----------------------------------------------------
+    const int r = lane & 15, h = lane >> 4;
+    uint32_t rv[4];
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+        uint32_t w = 0;
+#pragma unroll
+        for (int n = 0; n < 4; ++n) w |= (uint32_t)(4 * (16 * h + ((4 * v + n + r) & 15))) << (8 * n);
+        rv[v] = w;
+    }
+    float xsum = 0.0f;  // sum of the activations of this lane's 128-column block
+    if (Z) {
+#pragma unroll
+        for (int c = 0; c < 16; ++c) xsum += lut[255 * 64 + 16 * h + c];
+    }
+
+    // ---- stream the row tiles ----------------------------------------------------
+    // The split-K atomics are pipelined so that inside the loop no wave waits on a
+    // round trip to memory that started less than one tile of work earlier.  With k
+    // the tile computed in an iteration, the iteration
+    //   (a) waits for all outstanding memory operations of the wave: the loads of
+    //       tile k and the value returned by the atomic of tile k-2;
+    //   (b) completes the rows of tile k-2 for which that value shows the last arrival;
+    //   (c) issues the atomic of tile k-1, whose partial was kept in a register;
+    //   (d) starts the loads of tile k+1;  (e) computes tile k.
+    const bool split_k = p.nslice > 1;
+    int held_tile = -1;  // computed, partial still in `held`
+    float held = 0.0f;
+    int pend_tile = -1;  // atomic issued, result pending
+    unsigned long long pend_old = 0, pend_mine = 0;
+
+    for (int tile = t_begin; tile < t_end; ++tile) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // (a)
+        if (split_k && lane < 32) {
+            if (pend_tile >= 0) complete_row(p, pend_tile * kTileRows + lane, pend_old + pend_mine);  // (b)
+            pend_tile = held_tile;
+            if (held_tile >= 0) {  // (c)
+                pend_mine = encode_partial(held);
+                pend_old = __hip_atomic_fetch_add(p.accum + held_tile * kTileRows + lane, pend_mine,
+                                                  __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+        TileRegs<Q, Z> nxt;
+        tile_ptr += p.tile_bytes;
+        if (tile + 1 < t_end) load_tile<Q, Z>(nxt, tile_ptr, lane);  // (d)
+
+        float acc[2];  // (e)
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            float a = 0.0f;
+#pragma unroll
+            for (int i = 0; i < Q; ++i)
+                a = fmaf(scale_of<Q, Z>(cur, t, i), sign_sum16(lut, cur.planes[t][i], rv), a);
+            if (Z) a = fmaf(scale_of<Q, Z>(cur, t, Q), xsum, a);
+            // sum the four block owners (lanes r, r+16, r+32, r+48) of each row
+            a += __shfl_xor(a, 16, 64);
+            a += __shfl_xor(a, 32, 64);
+            acc[t] = a;
+        }
+        const float out = (lane & 16) ? acc[1] : acc[0];  // lanes 0..31 <-> rows 0..31 of the tile
+        if (split_k) {
+            held = out;
+            held_tile = tile;
+        } else {
+            const int row = tile * kTileRows + (lane & 31);
+            if (lane < 32 && row < p.M) p.y[row] = float_to_half_bits(out);
+        }
+        if (tile + 1 < t_end) cur = nxt;
+    }
+
+    if (split_k && lane < 32) {  // drain: two tiles may still be in the pipeline
+        if (held_tile >= 0) {
+            const unsigned long long mine = encode_partial(held);
+            const unsigned long long old = __hip_atomic_fetch_add(p.accum + held_tile * kTileRows + lane, mine,
+                                                                  __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (pend_tile >= 0) complete_row(p, pend_tile * kTileRows + lane, pend_old + pend_mine);
+            complete_row(p, held_tile * kTileRows + lane, old + mine);
+        } else if (pend_tile >= 0) {
+            complete_row(p, pend_tile * kTileRows + lane, pend_old + pend_mine);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------
+// host side
+// ---------------------------------------------------------------------------------
+constexpr int kGemvWaves = 4;             // waves per workgroup
+constexpr int kResidentGroups = 2 * 256;  // 64 KB LDS each: two workgroups per CU, 256 CUs
+
+int auto_row_split(const Geom &g)
+{
+    // Cost model: a wave's time = tiles it streams (+ a constant for the table
+    // build).  Prefer the split that minimises the longest wave while all
+    // workgroups are resident at once; on ties take fewer workgroups.
+    int max_split = kResidentGroups / g.nslice;
+    if (max_split < 1) max_split = 1;
+    int cap = (g.ntile + kGemvWaves - 1) / kGemvWaves;  // no more waves than tiles
+    if (max_split > cap) max_split = cap;
+    if (max_split < 1) max_split = 1;
+    int best = 1;
+    double best_cost = 1e30;
+    for (int s = 1; s <= max_split; ++s) {
+        int waves = s * kGemvWaves;
+        int longest = (g.ntile + waves - 1) / waves;
+        double cost = longest + 1.5;
+        if (cost < best_cost - 1e-9) { best_cost = cost; best = s; }
+    }
+    return best;
+}
+
+template <int Q, int Z>
+static hipError_t launch_qz(const Geom &g, const GemvParams &p, int row_split, hipStream_t stream)
+{
+    dim3 grid((unsigned)(g.nslice * row_split)), block(kGemvWaves * 64);
+    hipLaunchKernelGGL((bcq_gemv_kernel<Q, Z, kGemvWaves>), grid, block, 0, stream, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_gemv(const Geom &g, const void *packed, const uint16_t *x, uint16_t *y,
+                       void *workspace, int row_split, hipStream_t stream)
+{
+    if (row_split <= 0) row_split = auto_row_split(g);
+    GemvParams p;
+    p.blob = static_cast<const uint8_t *>(packed);
+    p.x = x;
+    p.y = y;
+    p.accum = static_cast<unsigned long long *>(workspace);
+    p.M = g.M; p.N = g.N; p.Mp = g.Mp;
+    p.ntile = g.ntile; p.nslice = g.nslice;
+    p.waves_per_slice = row_split * kGemvWaves;
+    p.tile_bytes = g.tile_bytes;
+    const int key = g.q * 2 + g.z;
+    switch (key) {
+        case 2: return launch_qz<1, 0>(g, p, row_split, stream);
+        case 3: return launch_qz<1, 1>(g, p, row_split, stream);
+        case 4: return launch_qz<2, 0>(g, p, row_split, stream);
+        case 5: return launch_qz<2, 1>(g, p, row_split, stream);
+        case 6: return launch_qz<3, 0>(g, p, row_split, stream);
+        case 7: return launch_qz<3, 1>(g, p, row_split, stream);
+        case 8: return launch_qz<4, 0>(g, p, row_split, stream);
+        case 9: return launch_qz<4, 1>(g, p, row_split, stream);
+    }
+    return hipErrorInvalidValue;
+}
+
+// ---------------------------------------------------------------------------------
+// streaming-read probe: same load width and a similar launch shape, no arithmetic
+// ---------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void read_probe_kernel(const u32x4 *__restrict__ buf, size_t n16,
+                                                         uint32_t *__restrict__ sink)
+{
+    // each workgroup reads one contiguous span, 4 KB per wave per step
+    size_t per_block = (n16 + gridDim.x - 1) / gridDim.x;
+    size_t begin = (size_t)blockIdx.x * per_block;
+    size_t end = begin + per_block < n16 ? begin + per_block : n16;
+    uint32_t acc = 0;
+    for (size_t i = begin + threadIdx.x; i < end; i += 256) {
+        u32x4 v = __builtin_nontemporal_load(buf + i);
+        acc ^= v.x ^ v.y ^ v.z ^ v.w;
+    }
+    acc ^= __shfl_xor(acc, 32, 64);
+    acc ^= __shfl_xor(acc, 16, 64);
+    acc ^= __shfl_xor(acc, 8, 64);
+    acc ^= __shfl_xor(acc, 4, 64);
+    acc ^= __shfl_xor(acc, 2, 64);
+    acc ^= __shfl_xor(acc, 1, 64);
+    __shared__ uint32_t part[4];
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) sink[blockIdx.x] = part[0] ^ part[1] ^ part[2] ^ part[3];
+}
+
+hipError_t launch_read_probe(const void *buf, size_t bytes, void *sink, hipStream_t stream)
+{
+    hipLaunchKernelGGL(read_probe_kernel, dim3(kProbeBlocks), dim3(256), 0, stream,
+                       static_cast<const u32x4 *>(buf), bytes / 16, static_cast<uint32_t *>(sink));
+    return hipGetLastError();
+}
+
+}  // namespace bcq

@@ -1,0 +1,25 @@
+// Internal declarations shared by the translation units of libbcq (not public).
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "../../include/bcq.h"
+#include "bcq_layout.h"
+
+namespace bcq {
+
+// Launchers; each returns the hipError_t of its last launch.
+hipError_t launch_pack(const Geom &g, const uint8_t *codes, const uint16_t *alpha,
+                       const uint16_t *offset, void *packed, hipStream_t stream);
+hipError_t launch_unpack(const Geom &g, const void *packed, uint8_t *codes, uint16_t *alpha,
+                         uint16_t *offset, hipStream_t stream);
+hipError_t launch_fill_zero(void *ptr, size_t bytes, hipStream_t stream);
+hipError_t launch_gemv(const Geom &g, const void *packed, const uint16_t *x, uint16_t *y,
+                       void *workspace, int row_split, hipStream_t stream);
+hipError_t launch_read_probe(const void *buf, size_t bytes, void *sink, hipStream_t stream);
+
+constexpr int kProbeBlocks = 2048;
+
+// Row split (workgroups per column slice) the GEMV uses when none is forced.
+int auto_row_split(const Geom &g);
+
+}  // namespace bcq

@@ -1,0 +1,86 @@
+// Internal geometry of the packed weight blob (layout version 1), shared by the
+// pack, GEMV and skinny kernels of this library.  Not part of the public ABI.
+//
+// The weight of Eq. 11 (q sign planes, per-group alpha, optional offset) is cut
+// into tiles of 32 rows x 512 columns.  A tile is what one 64-lane wavefront
+// consumes per step of the GEMV:
+//
+//   lane l = 16*h + r  (h = 0..3, r = 0..15) owns, for both row halves t = 0,1,
+//   the 128-column block kb = 4*slice + h of row 32*tile + 16*t + r.
+//
+//   tile bytes:
+//     [t][plane i][lane l]  16 bytes : the 128 sign bits of (row, block kb, plane i)
+//                                      byte j holds the 8 columns 128*kb + 8*c + (0..7),
+//                                      c = (j + r) mod 16, least-significant bit = lowest
+//                                      column.  The rotation by r makes the 16 lanes of a
+//                                      row group address 16 different LDS banks at every
+//                                      step of the table lookups.
+//     [lane l][t][sub][c]   2 bytes  : binary16 alpha_0..alpha_{q-1} (and the offset if
+//                                      present) of (row, block kb, sub-group sub); sub
+//                                      splits the 128 columns when group < 128, and the
+//                                      values are replicated when group > 128.
+//
+//   blob = tiles ordered by column slice first, then by row tile, so that a
+//   workgroup, which owns one column slice, streams consecutive memory.
+//
+// Rows >= M and columns >= N are padding: zero bits, zero alpha, zero offset.
+#pragma once
+#include <stddef.h>
+#include <stdint.h>
+
+#if defined(__HIPCC__)
+#define BCQ_HD __host__ __device__
+#else
+#define BCQ_HD
+#endif
+
+namespace bcq {
+
+constexpr int kTileRows = 32;    // rows per tile (two halves of 16)
+constexpr int kTileCols = 512;   // columns per tile = per column slice (4 blocks of 128)
+constexpr int kBlockCols = 128;  // columns owned by one lane per plane (one 128-bit load)
+constexpr int kChunkCols = 8;    // columns per lookup-table index
+constexpr int kMaxQ = 4;
+
+struct Geom {
+    int M, N, q, z, group;
+    int sub;        // scale sub-groups per 128-column block: 128/group for group 32 or 64
+                    // (unless the row is one group), else 1
+    int nsc;        // binary16 scale entries per (row, block): sub * (q + z)
+    int Mp, Np;     // padded sizes
+    int ntile;      // row tiles   = Mp / 32
+    int nslice;     // col slices  = Np / 512
+    unsigned tile_plane_bytes;  // 2 * q * 64 * 16
+    unsigned tile_bytes;        // plane bytes + 64 * 2 * nsc * 2
+};
+
+BCQ_HD inline Geom make_geom(int M, int N, int q, int group, int has_offset)
+{
+    Geom g;
+    g.M = M; g.N = N; g.q = q; g.z = has_offset ? 1 : 0; g.group = group;
+    g.sub = (group % kBlockCols == 0 || group == N) ? 1 : kBlockCols / group;
+    g.nsc = g.sub * (q + g.z);
+    g.Mp = (M + kTileRows - 1) / kTileRows * kTileRows;
+    g.Np = (N + kTileCols - 1) / kTileCols * kTileCols;
+    g.ntile = g.Mp / kTileRows;
+    g.nslice = g.Np / kTileCols;
+    g.tile_plane_bytes = 2u * q * 64u * 16u;
+    g.tile_bytes = g.tile_plane_bytes + 64u * 2u * g.nsc * 2u;
+    return g;
+}
+
+BCQ_HD inline size_t tile_offset(const Geom &g, int slice, int tile)
+{
+    return ((size_t)slice * g.ntile + tile) * g.tile_bytes;
+}
+
+// Workspace: one 64-bit split-K accumulator word per padded row and batch column.
+// Its arrival count has 10 bits, so at most 1023 column slices.
+constexpr int kMaxSlices = 1023;
+
+BCQ_HD inline size_t ws_bytes(const Geom &g, int batch)
+{
+    return g.nslice == 1 ? 0 : (size_t)batch * g.Mp * 8;
+}
+
+}  // namespace bcq

@@ -1,0 +1,124 @@
+"""CPU-side checks of the C ABI: the library loads, exports every symbol the
+header declares, sizes are right, and every argument check fires before any
+launch (so none of this needs a GPU)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2407_02891_amd as bcq
+from paper_2407_02891_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def header_symbols():
+    text = open(os.path.join(ROOT, "include", "bcq.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(bcq_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = bcq.lib()
+    syms = header_symbols()
+    assert set(syms) == set(B.EXPORTS)
+    for s in syms:
+        assert hasattr(L, s), s
+
+
+def test_status_strings():
+    assert bcq.status_string(0) == "ok"
+    for s in range(1, 5):
+        assert bcq.status_string(s) not in ("ok", "unknown status")
+    assert bcq.status_string(99) == "unknown status"
+
+
+def test_packed_bytes_equals_algorithmic_bytes_on_unpadded_shapes():
+    for (M, N, q, z) in [(7168, 28672, 3, 0), (28672, 7168, 3, 0), (7168, 7168, 2, 1), (9216, 36864, 3, 0), (8192, 8192, 2, 0)]:
+        d = bcq.Desc(M, N, q, 128, z, 0)
+        G = N // 128
+        want = q * M * N // 8 + q * M * G * 2 + z * M * G * 2
+        assert bcq.packed_bytes(d) == want
+
+
+def test_packed_bytes_pads_ragged_shapes():
+    d = bcq.Desc(768, 768, 3, 128, 0, 0)              # N padded to 1024
+    assert bcq.packed_bytes(d) == 2 * 24 * (2 * 3 * 1024 + 64 * 2 * 3 * 2)
+    assert bcq.workspace_bytes(d, 1) == 768 * 8
+    d1 = bcq.Desc(100, 512, 3, 128, 0, 0)             # single column slice: no split-K workspace
+    assert bcq.workspace_bytes(d1, 1) == 0
+
+
+@pytest.mark.parametrize("fields,status", [
+    ((0, 128, 3, 128, 0), B.BCQ_ERR_INVALID_ARG),
+    ((16, 100, 3, 100, 0), B.BCQ_ERR_INVALID_ARG),      # N not a multiple of 32
+    ((16, 256, 0, 128, 0), B.BCQ_ERR_INVALID_ARG),
+    ((16, 256, 3, 96, 0), B.BCQ_ERR_INVALID_ARG),       # group does not divide N
+    ((16, 256, 3, 128, 2), B.BCQ_ERR_INVALID_ARG),
+    ((16, 256, 5, 128, 0), B.BCQ_ERR_UNSUPPORTED),      # q > 4
+    ((16, 384, 3, 96, 0), B.BCQ_ERR_UNSUPPORTED),       # group neither k*128 nor N
+    ((16, 384, 3, 64, 0), B.BCQ_ERR_UNSUPPORTED),
+])
+def test_bad_descriptors_are_refused_before_launch(fields, status):
+    d = bcq.Desc(*fields, 0)
+    assert bcq.packed_bytes(d) == 0
+    assert bcq.workspace_bytes(d, 1) == 0
+    L = bcq.lib()
+    # non-NULL dummy pointers: validation must fail before they are ever used
+    rc = L.bcq_pack(ctypes.byref(d), 256, 256, None, 256, None)
+    assert rc == status
+
+
+def test_gemv_argument_checks():
+    L = bcq.lib()
+    d = bcq.Desc(64, 1024, 3, 128, 0, 0)
+    ok = 0x1000
+    assert L.bcq_gemv(ctypes.byref(d), ok, ok, ok, ok, None) == B.BCQ_ERR_INVALID_ARG   # not packed yet
+    d.layout_version = B.BCQ_LAYOUT_VERSION
+    assert L.bcq_gemv(None, ok, ok, ok, ok, None) == B.BCQ_ERR_INVALID_ARG
+    assert L.bcq_gemv(ctypes.byref(d), None, ok, ok, ok, None) == B.BCQ_ERR_INVALID_ARG
+    assert L.bcq_gemv(ctypes.byref(d), ok, None, ok, ok, None) == B.BCQ_ERR_INVALID_ARG
+    assert L.bcq_gemv(ctypes.byref(d), ok, ok, None, ok, None) == B.BCQ_ERR_INVALID_ARG
+    assert L.bcq_gemv(ctypes.byref(d), ok + 16, ok, ok, ok, None) == B.BCQ_ERR_INVALID_ARG  # blob not 256-aligned
+    assert L.bcq_gemv(ctypes.byref(d), ok, ok + 2, ok, ok, None) == B.BCQ_ERR_INVALID_ARG   # x not 16-aligned
+    assert L.bcq_gemv(ctypes.byref(d), ok, ok, ok + 1, ok, None) == B.BCQ_ERR_INVALID_ARG   # y not 2-aligned
+    assert L.bcq_gemv(ctypes.byref(d), ok, ok, ok, None, None) == B.BCQ_ERR_WORKSPACE
+    assert L.bcq_gemv(ctypes.byref(d), ok, ok, ok, ok + 4, None) == B.BCQ_ERR_WORKSPACE
+
+
+def test_skinny_argument_checks():
+    L = bcq.lib()
+    d = bcq.Desc(64, 1024, 3, 128, 0, B.BCQ_LAYOUT_VERSION)
+    ok = 0x1000
+    f = lambda ldx, ldy, b: L.bcq_gemm_skinny(ctypes.byref(d), ok, ok, ldx, ok, ldy, b, ok, None)
+    assert f(1024, 64, 0) == B.BCQ_ERR_INVALID_ARG
+    assert f(1024, 64, 17) == B.BCQ_ERR_INVALID_ARG
+    assert f(1016, 64, 2) == B.BCQ_ERR_INVALID_ARG     # ldx < N
+    assert f(1028, 64, 2) == B.BCQ_ERR_INVALID_ARG     # ldx not a multiple of 8
+    assert f(1024, 63, 2) == B.BCQ_ERR_INVALID_ARG     # ldy < M
+
+
+def test_pack_pointer_checks():
+    L = bcq.lib()
+    d = bcq.Desc(64, 1024, 3, 128, 1, 0)
+    ok = 0x1000
+    assert L.bcq_pack(ctypes.byref(d), ok, ok, None, ok, None) == B.BCQ_ERR_INVALID_ARG   # offset missing
+    d0 = bcq.Desc(64, 1024, 3, 128, 0, 0)
+    assert L.bcq_pack(ctypes.byref(d0), ok, ok, ok, ok, None) == B.BCQ_ERR_INVALID_ARG    # offset unexpected
+    assert L.bcq_pack(ctypes.byref(d0), None, ok, None, ok, None) == B.BCQ_ERR_INVALID_ARG
+    assert L.bcq_pack(ctypes.byref(d0), ok, ok, None, ok + 128, None) == B.BCQ_ERR_INVALID_ARG
+    assert d0.layout_version == 0
+
+
+def test_misc_argument_checks():
+    L = bcq.lib()
+    assert L.bcq_workspace_init(None, 64, None) == B.BCQ_ERR_INVALID_ARG
+    assert L.bcq_workspace_init(None, 0, None) == B.BCQ_OK
+    assert L.bcq_workspace_init(0x1008, 64, None) == B.BCQ_ERR_INVALID_ARG
+    assert L.bcq_read_probe(None, 64, 0x1000, None) == B.BCQ_ERR_INVALID_ARG
+    assert L.bcq_read_probe(0x1000, 24, 0x1000, None) == B.BCQ_ERR_INVALID_ARG
+    assert L.bcq_set_option(b"no_such_option", 1) == B.BCQ_ERR_INVALID_ARG
+    assert L.bcq_set_option(b"row_split", -1) == B.BCQ_ERR_INVALID_ARG
+    assert L.bcq_set_option(b"row_split", 0) == B.BCQ_OK
+    assert B.read_probe_sink_bytes() >= 4

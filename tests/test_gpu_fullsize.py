@@ -1,0 +1,50 @@
+"""GPU parity at the benchmark's full layer sizes, in the launch configuration
+bench.py times (automatic row split).  The oracle evaluates a sample of rows
+(first and last row tiles plus random rows) one by one."""
+import numpy as np
+import pytest
+
+import bcq_synth
+from tests import gpu_util as U
+
+pytestmark = pytest.mark.gpu
+
+
+def _sample_rows(M, n=192, seed=0):
+    rng = np.random.default_rng(seed)
+    rows = set(range(0, 32)) | set(range(M - 32, M)) | set(rng.choice(M, size=min(n, M), replace=False).tolist())
+    return np.array(sorted(rows))
+
+
+def _check(M, N, q, offset, batch=1, **kw):
+    L = bcq_synth.make_layer(M, N, q, group=128, offset=offset, batch=batch, seed=0, **kw)
+    pl = U.upload_and_pack(L, max_batch=batch)
+    xd = U.x_dev(L)
+    y = U.gpu_gemv(pl, xd)[None, :] if batch == 1 else U.gpu_gemm(pl, xd)
+    rows = _sample_rows(M)
+    y_ref = U.oracle_rows(L, rows)
+    worst, normwise = U.gate(y[:, rows], y_ref, f"{M}x{N} q={q} z={offset} b={batch}")
+    print(f"{M}x{N} q={q} z={offset} b={batch}: gated {worst:.2e} normwise {normwise:.2e}")
+
+
+@pytest.mark.parametrize("M,N", [(7168, 7168), (28672, 7168), (7168, 28672)])
+def test_opt30b_q3(M, N):
+    """configs[1]"""
+    _check(M, N, 3, False)
+
+
+@pytest.mark.parametrize("M,N", [(7168, 7168), (7168, 28672)])
+def test_opt30b_q2_offset(M, N):
+    """configs[2], batch 1"""
+    _check(M, N, 2, True)
+
+
+def test_opt66b_q3_outliers():
+    """configs[3], batch 1, the widest layer"""
+    _check(9216, 36864, 3, False, outlier_frac=0.01)
+
+
+@pytest.mark.parametrize("M,N,q", [(1024, 8192, 3), (8192, 28672, 2)])
+def test_llama70b_shapes(M, N, q):
+    """configs[4]: GQA k/v projection and the down projection"""
+    _check(M, N, q, False)

@@ -1,0 +1,142 @@
+"""GPU parity: bcq_pack + bcq_gemv / bcq_gemm_skinny through the C ABI against
+the fp64 oracle, element by element, on the same seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+import bcq_synth
+import paper_2407_02891_amd as bcq
+from oracle import ref
+from tests import gpu_util as U
+
+pytestmark = pytest.mark.gpu
+
+
+def _run_case(M, N, q, group, offset, batch=1, seed=0, **kw):
+    L = bcq_synth.make_layer(M, N, q, group=group, offset=offset, batch=batch, seed=seed, **kw)
+    pl = U.upload_and_pack(L, max_batch=batch)
+    xd = U.x_dev(L)
+    y_ref = ref.gemm(L.planes, L.alpha, L.offset, L.x)
+    if batch == 1:
+        y = U.gpu_gemv(pl, xd)[None, :]
+    else:
+        y = U.gpu_gemm(pl, xd)
+    return U.gate(y, y_ref, f"M={M} N={N} q={q} g={group} z={offset} b={batch}")
+
+
+def test_config0_768x768_q3():
+    """configs[0]: 768x768, q=3, group 128, no offset, batch 1, seed 0."""
+    worst, normwise = _run_case(768, 768, 3, 128, False)
+    print(f"config0 gated {worst:.2e} normwise {normwise:.2e}")
+
+
+@pytest.mark.parametrize("q", [1, 2, 3, 4])
+@pytest.mark.parametrize("offset", [False, True])
+def test_planes_and_offset(q, offset):
+    _run_case(256, 1536, q, 128, offset, seed=q)
+
+
+@pytest.mark.parametrize("M,N", [(1, 32), (31, 96), (33, 544), (100, 1120), (257, 2080), (1000, 512), (64, 4096)])
+def test_ragged_shapes(M, N):
+    """Rows not a multiple of 32, columns not a multiple of 512 (padded tiles),
+    single-slice and many-slice cases."""
+    group = 128 if N % 128 == 0 else N
+    _run_case(M, N, 3, group, True, seed=M)
+
+
+@pytest.mark.parametrize("group", [128, 256, 512, 2048])
+def test_group_sizes_multiple_of_128(group):
+    _run_case(96, 2048, 3, group, True, seed=group)
+    _run_case(96, 2048, 2, group, False, seed=group + 1)
+
+
+def test_exact_inputs_bit_for_bit():
+    """alpha powers of two, integer x and offset: fp16/fp32/fp64 are all exact,
+    so the GPU result must equal the oracle exactly (any difference is an
+    indexing error), across slices, ragged edges and split-K."""
+    for (M, N, q, off) in [(96, 1536, 3, True), (130, 2592 - 32, 2, False), (64, 512, 3, True), (2048, 1024, 3, False)]:
+        group = 128 if N % 128 == 0 else N
+        L = bcq_synth.make_exact_layer(M, N, q, group=group, offset=off, seed=M + q)
+        pl = U.upload_and_pack(L)
+        y = U.gpu_gemv(pl, U.x_dev(L)).astype(np.float64)
+        y_ref = ref.gemm(L.planes, L.alpha, L.offset, L.x)[0]
+        assert np.abs(y_ref).max() < 2048, "test inputs must stay exactly representable in fp16"
+        assert np.array_equal(y, y_ref), (M, N, q, off, np.abs(y - y_ref).max())
+
+
+def test_pack_unpack_identity():
+    L = bcq_synth.make_layer(100, 1120, 3, group=1120, offset=True, seed=9)
+    pl = U.upload_and_pack(L)
+    codes = torch.empty((L.M, L.N), dtype=torch.uint8, device="cuda")
+    alpha = torch.empty((L.M, 1, L.q), dtype=torch.float16, device="cuda")
+    off = torch.empty((L.M, 1), dtype=torch.float16, device="cuda")
+    bcq.unpack(pl.desc, pl.packed, codes, alpha, off)
+    torch.cuda.synchronize()
+    assert np.array_equal(codes.cpu().numpy(), L.codes())
+    assert np.array_equal(alpha.cpu().numpy().view(np.uint16), L.alpha.view(np.uint16))
+    assert np.array_equal(off.cpu().numpy().view(np.uint16), L.offset.view(np.uint16))
+
+
+def test_repeated_calls_are_deterministic_and_workspace_self_resets():
+    L = bcq_synth.make_layer(512, 4096, 3, group=128, offset=False, seed=21)
+    pl = U.upload_and_pack(L)
+    xd = U.x_dev(L)
+    first = U.gpu_gemv(pl, xd).view(np.uint16)
+    for _ in range(20):
+        again = U.gpu_gemv(pl, xd).view(np.uint16)
+        assert np.array_equal(first, again)
+    assert not pl.workspace.cpu().numpy().any(), "split-K accumulators must be zero again after a call"
+
+
+def test_row_split_does_not_change_results():
+    L = bcq_synth.make_layer(700, 3072, 3, group=128, offset=True, seed=33)
+    pl = U.upload_and_pack(L)
+    xd = U.x_dev(L)
+    outs = []
+    try:
+        for split in (1, 2, 5, 0):
+            bcq.set_option("row_split", split)
+            outs.append(U.gpu_gemv(pl, xd).view(np.uint16).copy())
+    finally:
+        bcq.set_option("row_split", 0)
+    for o in outs[1:]:
+        assert np.array_equal(outs[0], o)
+    U.gate(outs[0].view(np.float16)[None, :], ref.gemm(L.planes, L.alpha, L.offset, L.x))
+
+
+def test_subnormal_alpha_and_zero_inputs():
+    L = bcq_synth.make_layer(64, 1024, 3, group=128, offset=False, seed=5)
+    a = L.alpha.view(np.uint16).copy()
+    a[:, :, 2] = 0x0001                      # smallest subnormal in the last plane
+    a[:, :, 1] = 0x03FF                      # largest subnormal
+    L.alpha = a.view(np.float16)
+    pl = U.upload_and_pack(L)
+    y = U.gpu_gemv(pl, U.x_dev(L))
+    U.gate(y[None, :], ref.gemm(L.planes, L.alpha, None, L.x))
+    # all-zero activations give exactly zero
+    xz = torch.zeros(L.N, dtype=torch.float16, device="cuda")
+    assert not U.gpu_gemv(pl, xz).view(np.uint16).any()
+
+
+@pytest.mark.parametrize("batch", [2, 4, 8, 16])
+def test_skinny_batches(batch):
+    _run_case(160, 1536, 3, 128, True, batch=batch, seed=batch)
+    _run_case(96, 1024, 2, 128, False, batch=batch, seed=batch + 50)
+
+
+def test_skinny_strided_rows():
+    L = bcq_synth.make_layer(128, 1024, 3, group=128, offset=True, batch=3, seed=77)
+    pl = U.upload_and_pack(L, max_batch=3)
+    Xbig = torch.zeros((3, L.N + 64), dtype=torch.float16, device="cuda")
+    Xbig[:, : L.N] = U.x_dev(L)
+    Ybig = torch.full((3, L.M + 7), 123.0, dtype=torch.float16, device="cuda")
+    bcq.gemm_skinny(pl.desc, pl.packed, Xbig, Xbig.stride(0), Ybig, Ybig.stride(0), 3, pl.workspace)
+    torch.cuda.synchronize()
+    Y = Ybig.cpu().numpy()
+    U.gate(Y[:, : L.M], ref.gemm(L.planes, L.alpha, L.offset, L.x))
+    assert np.all(Y[:, L.M:] == 123.0), "columns beyond M must not be written"
+
+
+def test_outlier_channels():
+    """configs[3] activation recipe: 1% of channels scaled x20."""
+    _run_case(512, 9216, 3, 128, False, seed=3, outlier_frac=0.01)
