@@ -8,7 +8,7 @@ using namespace bcq;
 
 namespace {
 
-int g_row_split = 0;  // 0 = automatic
+GemvTuning g_tuning;  // zeros = automatic
 
 bool desc_ok(const bcq_desc *d, bcq_status *why)
 {
@@ -109,7 +109,7 @@ bcq_status bcq_gemm_skinny(const bcq_desc *desc, const void *packed, const uint1
     // One pass of the table kernel per activation row (launches on one stream
     // run in order, so they can share the workspace).
     for (int j = 0; j < batch; ++j) {
-        if (launch_gemv(g, packed, X + (size_t)j * ldx, Y + (size_t)j * ldy, workspace, g_row_split, s) != hipSuccess)
+        if (launch_gemv(g, packed, X + (size_t)j * ldx, Y + (size_t)j * ldy, workspace, g_tuning, s) != hipSuccess)
             return BCQ_ERR_HIP;
     }
     return BCQ_OK;
@@ -135,8 +135,16 @@ bcq_status bcq_read_probe(const void *buf, size_t bytes, void *sink, void *strea
 bcq_status bcq_set_option(const char *name, int32_t value)
 {
     if (!name || value < 0) return BCQ_ERR_INVALID_ARG;
-    if (strcmp(name, "row_split") == 0) {
-        g_row_split = value;
+    if (strcmp(name, "workgroups") == 0) {
+        g_tuning.workgroups = value;
+        return BCQ_OK;
+    }
+    if (strcmp(name, "waves") == 0 && (value == 0 || value == 4 || value == 8)) {
+        g_tuning.waves = value;
+        return BCQ_OK;
+    }
+    if (strcmp(name, "probe") == 0 && value <= 1) {
+        g_tuning.probe = value;
         return BCQ_OK;
     }
     return BCQ_ERR_INVALID_ARG;

@@ -10,7 +10,7 @@
 //  * A workgroup owns one column slice of 512 activations.  It first builds, in
 //    LDS, one 256-entry fp32 table per 8 consecutive activations ("chunk"):
 //    table[c][p] = sum_{b<8} (bit b of p ? +x : -x)[8c+b]  (the sign-sum lookup
-//    idea of the LUT-GEMM kernel the paper cites, re-laid out for a 64-bank-free
+//    idea of the LUT-GEMM kernel the paper cites, re-laid out for a conflict-free
 //    access pattern): entry p of chunk c sits at byte p*256 + 4*c, so a chunk
 //    lives in one LDS bank and the 64 chunks of the slice cover 64 dword columns.
 //  * Each lane owns one (row, 128-column block, plane) at a time: 16 bytes of
@@ -30,6 +30,13 @@
 //    order; the lane whose atomic returns the last arrival count owns the final
 //    sum (returned value + own term), rounds it to binary16, stores y and
 //    re-arms the word with zero.  No partial arrays, no fences, no second pass.
+//  * Each wave double-buffers its tiles in registers: the loads of tile k+1 and the
+//    split-K atomic of tile k-1 are in flight while tile k is computed; the value
+//    an atomic returns is looked at one iteration after it was issued.
+//  * The grid is exactly as large as the chip holds at once (two 64 KB-LDS
+//    workgroups on each of the 256 CUs) whenever the problem is big enough, with
+//    the column slices cut into unequal numbers of row parts to get there, so all
+//    CUs carry the same load.
 #include "bcq_internal.h"
 
 namespace bcq {
@@ -41,11 +48,28 @@ struct GemvParams {
     unsigned long long *accum;  // [Mp] fixed-point row accumulators (value << 10 | arrivals)
     int M, N, Mp;
     int ntile, nslice;
-    int waves_per_slice;  // row_split * NW
+    int parts, big_slices;  // slices [0, big_slices) have parts+1 workgroups, the others parts
     unsigned tile_bytes;
+#ifdef BCQ_TRACE
+    unsigned long long *trace;  // per wave 16 timestamps (100 MHz), development builds only
+#endif
 };
 
+#ifdef BCQ_TRACE
+#define BCQ_TRACE_DECL unsigned long long trace_t[16] = {0}; int trace_n = 0;
+#define BCQ_TRACE_POINT() do { if (trace_n < 16) trace_t[trace_n++] = wall_clock64(); } while (0)
+#define BCQ_TRACE_DUMP() do { if (p.trace && lane == 0) for (int i = 0; i < 16; ++i) \
+        p.trace[((size_t)blockIdx.x * NW + wave) * 16 + i] = trace_t[i]; } while (0)
+#else
+#define BCQ_TRACE_DECL
+#define BCQ_TRACE_POINT() do {} while (0)
+#define BCQ_TRACE_DUMP() do {} while (0)
+#endif
+
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef unsigned int u32x3 __attribute__((ext_vector_type(3)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));  // one 128-bit load
+typedef unsigned int u32x16 __attribute__((ext_vector_type(16)));  // one scalar load of 64 bytes
 
 __device__ __forceinline__ float half_bits_to_float(uint32_t bits16)
 {
@@ -149,24 +173,39 @@ __global__ __launch_bounds__(NW * 64) void bcq_gemv_kernel(GemvParams p)
 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
-    const int slice = blockIdx.x % p.nslice;
-    const int part = blockIdx.x / p.nslice;
+    BCQ_TRACE_DECL
+    BCQ_TRACE_POINT();  // start
+    int slice, part, parts;
+    {
+        const int big_groups = p.big_slices * (p.parts + 1);
+        if ((int)blockIdx.x < big_groups) {
+            parts = p.parts + 1;
+            slice = blockIdx.x / parts;
+            part = blockIdx.x - slice * parts;
+        } else {
+            parts = p.parts;
+            const int rest = blockIdx.x - big_groups;
+            slice = p.big_slices + rest / parts;
+            part = rest - (rest / parts) * parts;
+        }
+    }
+    const int waves_per_slice = parts * NW;
 
     // Row tiles of this wave: an even split of the ntile tiles over all waves of the slice.
     const int gw = part * NW + wave;
-    const int t_begin = (int)(((long long)gw * p.ntile) / p.waves_per_slice);
-    const int t_end = (int)(((long long)(gw + 1) * p.ntile) / p.waves_per_slice);
+    const int t_begin = (int)(((long long)gw * p.ntile) / waves_per_slice);
+    const int t_end = (int)(((long long)(gw + 1) * p.ntile) / waves_per_slice);
     const uint8_t *tile_ptr = p.blob + ((size_t)slice * p.ntile + t_begin) * p.tile_bytes;
 
     // Start the first tile's loads before building the tables.
     TileRegs<Q, Z> cur;
+    const int col0 = slice * kTileCols + kChunkCols * lane;  // lane = chunk
+    u32x4 xr = {0u, 0u, 0u, 0u};
+    if (col0 < p.N) xr = *reinterpret_cast<const u32x4 *>(p.x + col0);
     if (t_begin < t_end) load_tile<Q, Z>(cur, tile_ptr, lane);
 
     // ---- sign-sum tables for the 512 activations of this slice ----------------
     {
-        const int col0 = slice * kTileCols + kChunkCols * lane;  // lane = chunk
-        u32x4 xr = {0u, 0u, 0u, 0u};
-        if (col0 < p.N) xr = *reinterpret_cast<const u32x4 *>(p.x + col0);
         float xv[8];
         xv[0] = half_bits_to_float(xr.x & 0xffffu); xv[1] = half_bits_to_float(xr.x >> 16);
         xv[2] = half_bits_to_float(xr.y & 0xffffu); xv[3] = half_bits_to_float(xr.y >> 16);
@@ -193,7 +232,9 @@ __global__ __launch_bounds__(NW * 64) void bcq_gemv_kernel(GemvParams p)
             for (int a = 0; a < 8; ++a) lut[(wave * IPW + m * 8 + a) * 64 + lane] = lo[a] + mid;
         }
     }
+    BCQ_TRACE_POINT();  // tables written
     __syncthreads();
+    BCQ_TRACE_POINT();  // barrier passed
 
     // ---- per-lane constants ----------------------------------------------------
     const int r = lane & 15, h = lane >> 4;
@@ -228,6 +269,7 @@ __global__ __launch_bounds__(NW * 64) void bcq_gemv_kernel(GemvParams p)
 
     for (int tile = t_begin; tile < t_end; ++tile) {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // (a)
+        BCQ_TRACE_POINT();  // tile arrived
         if (split_k && lane < 32) {
             if (pend_tile >= 0) complete_row(p, pend_tile * kTileRows + lane, pend_old + pend_mine);  // (b)
             pend_tile = held_tile;
@@ -255,6 +297,7 @@ __global__ __launch_bounds__(NW * 64) void bcq_gemv_kernel(GemvParams p)
             acc[t] = a;
         }
         const float out = (lane & 16) ? acc[1] : acc[0];  // lanes 0..31 <-> rows 0..31 of the tile
+        BCQ_TRACE_POINT();  // tile computed
         if (split_k) {
             held = out;
             held_tile = tile;
@@ -276,66 +319,70 @@ __global__ __launch_bounds__(NW * 64) void bcq_gemv_kernel(GemvParams p)
             complete_row(p, pend_tile * kTileRows + lane, pend_old + pend_mine);
         }
     }
+    BCQ_TRACE_POINT();  // end
+    BCQ_TRACE_DUMP();
 }
 
 // ---------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------
-constexpr int kGemvWaves = 4;             // waves per workgroup
 constexpr int kResidentGroups = 2 * 256;  // 64 KB LDS each: two workgroups per CU, 256 CUs
 
-int auto_row_split(const Geom &g)
+int auto_workgroups(const Geom &g, int waves_per_group)
 {
-    // Cost model: a wave's time = tiles it streams (+ a constant for the table
-    // build).  Prefer the split that minimises the longest wave while all
-    // workgroups are resident at once; on ties take fewer workgroups.
-    int max_split = kResidentGroups / g.nslice;
-    if (max_split < 1) max_split = 1;
-    int cap = (g.ntile + kGemvWaves - 1) / kGemvWaves;  // no more waves than tiles
-    if (max_split > cap) max_split = cap;
-    if (max_split < 1) max_split = 1;
-    int best = 1;
-    double best_cost = 1e30;
-    for (int s = 1; s <= max_split; ++s) {
-        int waves = s * kGemvWaves;
-        int longest = (g.ntile + waves - 1) / waves;
-        double cost = longest + 1.5;
-        if (cost < best_cost - 1e-9) { best_cost = cost; best = s; }
-    }
-    return best;
+    // All workgroups resident at once and doing equal work; at least one tile per wave.
+    long long tiles = (long long)g.nslice * g.ntile;
+    long long groups = (tiles + waves_per_group - 1) / waves_per_group;
+    if (groups > kResidentGroups) groups = kResidentGroups;
+    if (groups < 1) groups = 1;
+    return (int)groups;
 }
 
-template <int Q, int Z>
-static hipError_t launch_qz(const Geom &g, const GemvParams &p, int row_split, hipStream_t stream)
+template <int Q, int Z, int NW>
+static hipError_t launch_one(const GemvParams &p, int groups, hipStream_t stream)
 {
-    dim3 grid((unsigned)(g.nslice * row_split)), block(kGemvWaves * 64);
-    hipLaunchKernelGGL((bcq_gemv_kernel<Q, Z, kGemvWaves>), grid, block, 0, stream, p);
+    hipLaunchKernelGGL((bcq_gemv_kernel<Q, Z, NW>), dim3((unsigned)groups), dim3(NW * 64), 0,
+                       stream, p);
     return hipGetLastError();
 }
 
-hipError_t launch_gemv(const Geom &g, const void *packed, const uint16_t *x, uint16_t *y,
-                       void *workspace, int row_split, hipStream_t stream)
+template <int Q, int Z>
+static hipError_t launch_qz(const GemvParams &p, const GemvTuning &t, int groups, hipStream_t stream)
 {
-    if (row_split <= 0) row_split = auto_row_split(g);
+    return t.waves == 8 ? launch_one<Q, Z, 8>(p, groups, stream) : launch_one<Q, Z, 4>(p, groups, stream);
+}
+
+hipError_t launch_gemv(const Geom &g, const void *packed, const uint16_t *x, uint16_t *y,
+                       void *workspace, const GemvTuning &t, hipStream_t stream)
+{
+    const int nw = t.waves == 8 ? 8 : 4;
+    int groups = t.workgroups > 0 ? t.workgroups : auto_workgroups(g, nw);
+    // at least one workgroup per slice, at most one per row tile of a slice
+    if (groups < g.nslice) groups = g.nslice;
+    if ((long long)groups > (long long)g.nslice * g.ntile) groups = g.nslice * g.ntile;
     GemvParams p;
+    p.parts = groups / g.nslice;
+    p.big_slices = groups % g.nslice;
     p.blob = static_cast<const uint8_t *>(packed);
     p.x = x;
     p.y = y;
     p.accum = static_cast<unsigned long long *>(workspace);
     p.M = g.M; p.N = g.N; p.Mp = g.Mp;
     p.ntile = g.ntile; p.nslice = g.nslice;
-    p.waves_per_slice = row_split * kGemvWaves;
-    p.tile_bytes = g.tile_bytes;
+    p.tile_bytes = (t.probe & 1) ? 0u : g.tile_bytes;
+#ifdef BCQ_TRACE
+    p.trace = t.trace;
+#endif
     const int key = g.q * 2 + g.z;
     switch (key) {
-        case 2: return launch_qz<1, 0>(g, p, row_split, stream);
-        case 3: return launch_qz<1, 1>(g, p, row_split, stream);
-        case 4: return launch_qz<2, 0>(g, p, row_split, stream);
-        case 5: return launch_qz<2, 1>(g, p, row_split, stream);
-        case 6: return launch_qz<3, 0>(g, p, row_split, stream);
-        case 7: return launch_qz<3, 1>(g, p, row_split, stream);
-        case 8: return launch_qz<4, 0>(g, p, row_split, stream);
-        case 9: return launch_qz<4, 1>(g, p, row_split, stream);
+        case 2: return launch_qz<1, 0>(p, t, groups, stream);
+        case 3: return launch_qz<1, 1>(p, t, groups, stream);
+        case 4: return launch_qz<2, 0>(p, t, groups, stream);
+        case 5: return launch_qz<2, 1>(p, t, groups, stream);
+        case 6: return launch_qz<3, 0>(p, t, groups, stream);
+        case 7: return launch_qz<3, 1>(p, t, groups, stream);
+        case 8: return launch_qz<4, 0>(p, t, groups, stream);
+        case 9: return launch_qz<4, 1>(p, t, groups, stream);
     }
     return hipErrorInvalidValue;
 }

@@ -13,13 +13,22 @@ hipError_t launch_pack(const Geom &g, const uint8_t *codes, const uint16_t *alph
 hipError_t launch_unpack(const Geom &g, const void *packed, uint8_t *codes, uint16_t *alpha,
                          uint16_t *offset, hipStream_t stream);
 hipError_t launch_fill_zero(void *ptr, size_t bytes, hipStream_t stream);
+// Launch shape of the GEMV (bcq_set_option); zeros mean "choose automatically".
+struct GemvTuning {
+    int workgroups = 0; // grid size
+    int waves = 0;      // waves per workgroup: 4 or 8
+    int probe = 0;      // timing experiment (wrong results): 1 = every tile re-reads tile 0
+#ifdef BCQ_TRACE
+    unsigned long long *trace = nullptr;  // development builds: per-wave timestamps
+#endif
+};
 hipError_t launch_gemv(const Geom &g, const void *packed, const uint16_t *x, uint16_t *y,
-                       void *workspace, int row_split, hipStream_t stream);
+                       void *workspace, const GemvTuning &tuning, hipStream_t stream);
 hipError_t launch_read_probe(const void *buf, size_t bytes, void *sink, hipStream_t stream);
 
 constexpr int kProbeBlocks = 2048;
 
-// Row split (workgroups per column slice) the GEMV uses when none is forced.
-int auto_row_split(const Geom &g);
+// Grid size the GEMV uses when none is forced.
+int auto_workgroups(const Geom &g, int waves_per_group);
 
 }  // namespace bcq

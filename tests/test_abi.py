@@ -119,6 +119,6 @@ def test_misc_argument_checks():
     assert L.bcq_read_probe(None, 64, 0x1000, None) == B.BCQ_ERR_INVALID_ARG
     assert L.bcq_read_probe(0x1000, 24, 0x1000, None) == B.BCQ_ERR_INVALID_ARG
     assert L.bcq_set_option(b"no_such_option", 1) == B.BCQ_ERR_INVALID_ARG
-    assert L.bcq_set_option(b"row_split", -1) == B.BCQ_ERR_INVALID_ARG
-    assert L.bcq_set_option(b"row_split", 0) == B.BCQ_OK
+    assert L.bcq_set_option(b"workgroups", -1) == B.BCQ_ERR_INVALID_ARG
+    assert L.bcq_set_option(b"workgroups", 0) == B.BCQ_OK
     assert B.read_probe_sink_bytes() >= 4

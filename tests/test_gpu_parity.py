@@ -88,17 +88,17 @@ def test_repeated_calls_are_deterministic_and_workspace_self_resets():
     assert not pl.workspace.cpu().numpy().any(), "split-K accumulators must be zero again after a call"
 
 
-def test_row_split_does_not_change_results():
+def test_grid_size_does_not_change_results():
     L = bcq_synth.make_layer(700, 3072, 3, group=128, offset=True, seed=33)
     pl = U.upload_and_pack(L)
     xd = U.x_dev(L)
     outs = []
     try:
-        for split in (1, 2, 5, 0):
-            bcq.set_option("row_split", split)
+        for split in (1, 2, 5, 37, 200, 0):
+            bcq.set_option("workgroups", split)
             outs.append(U.gpu_gemv(pl, xd).view(np.uint16).copy())
     finally:
-        bcq.set_option("row_split", 0)
+        bcq.set_option("workgroups", 0)
     for o in outs[1:]:
         assert np.array_equal(outs[0], o)
     U.gate(outs[0].view(np.float16)[None, :], ref.gemm(L.planes, L.alpha, L.offset, L.x))
