@@ -150,9 +150,12 @@ def main():
     roofline = dict(bound="hbm", kernel="bcq_gemv_kernel<3,0,4> on 7168x28672", achieved=round(achieved, 1),
                     peak=HBM_PEAK_GBS, unit="GB/s", frac=round(achieved / HBM_PEAK_GBS, 4),
                     bytes_per_launch=dom["weight_bytes"], us_per_launch=dom["us_per_gemv"], traffic=None)
-    traffic_file = os.path.join(ROOT, "profiles", "hbm_traffic_fc2.json")
-    if os.path.exists(traffic_file):  # measured separately with rocprofv3 --pmc, see profiles/
-        roofline["traffic"] = json.load(open(traffic_file)).get("hbm_bytes_per_launch")
+    # HBM bytes per launch measured separately with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE); see profiles/
+    traffic_file = os.path.join(ROOT, "profiles", "bcq_gemv_opt30b_q3_hbm_traffic.md")
+    if os.path.exists(traffic_file):
+        for line in open(traffic_file):
+            if line.startswith("hbm_bytes_per_launch_fc2"):
+                roofline["traffic"] = float(line.split("=")[1])
 
     # ---- oracle on the host cores, same layer set --------------------------------------
     cpu = None
