@@ -106,13 +106,10 @@ bcq_status bcq_gemm_skinny(const bcq_desc *desc, const void *packed, const uint1
     Geom g = geom_of(desc);
     if (workspace_bytes(g, batch) > 0 && (!workspace || !aligned(workspace, 16))) return BCQ_ERR_WORKSPACE;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    // One pass of the table kernel per activation row (launches on one stream
-    // run in order, so they can share the workspace).
-    for (int j = 0; j < batch; ++j) {
-        if (launch_gemv(g, packed, X + (size_t)j * ldx, Y + (size_t)j * ldy, workspace, g_tuning, s) != hipSuccess)
-            return BCQ_ERR_HIP;
-    }
-    return BCQ_OK;
+    // batch 1: the table-lookup GEMV (HBM-bound); batch >= 2: the matrix-core kernel, weights read once
+    hipError_t e = batch == 1 ? launch_gemv(g, packed, X, Y, workspace, g_tuning, s)
+                              : launch_skinny(g, packed, X, ldx, Y, ldy, batch, workspace, g_tuning.skinny_parts, s);
+    return e == hipSuccess ? BCQ_OK : BCQ_ERR_HIP;
 }
 
 bcq_status bcq_gemv(const bcq_desc *desc, const void *packed, const uint16_t *x, uint16_t *y, void *workspace,
@@ -141,6 +138,10 @@ bcq_status bcq_set_option(const char *name, int32_t value)
     }
     if (strcmp(name, "waves") == 0 && (value == 0 || value == 4 || value == 8)) {
         g_tuning.waves = value;
+        return BCQ_OK;
+    }
+    if (strcmp(name, "skinny_parts") == 0) {
+        g_tuning.skinny_parts = value;
         return BCQ_OK;
     }
     if (strcmp(name, "probe") == 0 && value <= 1) {

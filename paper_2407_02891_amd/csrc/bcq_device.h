@@ -1,0 +1,75 @@
+// Device-side helpers shared by the GEMV and skinny kernels (not public).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace bcq {
+
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef unsigned int u32x3 __attribute__((ext_vector_type(3)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));  // one 128-bit load
+
+__device__ __forceinline__ float half_bits_to_float(uint32_t bits16)
+{
+    return static_cast<float>(__builtin_bit_cast(_Float16, static_cast<uint16_t>(bits16)));
+}
+
+__device__ __forceinline__ uint16_t float_to_half_bits(float v)
+{
+    return __builtin_bit_cast(uint16_t, static_cast<_Float16>(v));  // round to nearest even
+}
+
+template <int Q, int Z>
+struct TileRegs {
+    u32x4 planes[2][Q];
+    uint32_t scales[Q + Z];  // binary16 pairs: [t][c] flattened, 2*(Q+Z) halves
+};
+
+template <int Q, int Z>
+__device__ __forceinline__ void load_tile(TileRegs<Q, Z> &r, const uint8_t *tile, int lane)
+{
+    const u32x4 *pp = reinterpret_cast<const u32x4 *>(tile) + lane;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int i = 0; i < Q; ++i) r.planes[t][i] = __builtin_nontemporal_load(pp + (t * Q + i) * 64);
+    const uint32_t *sp = reinterpret_cast<const uint32_t *>(tile + 2u * Q * 1024u) + lane * (Q + Z);
+#pragma unroll
+    for (int c = 0; c < Q + Z; ++c) r.scales[c] = __builtin_nontemporal_load(sp + c);
+}
+
+template <int Q, int Z>
+__device__ __forceinline__ float scale_of(const TileRegs<Q, Z> &r, int t, int c)
+{
+    int e = t * (Q + Z) + c;  // half index
+    uint32_t pair = r.scales[e >> 1];
+    return half_bits_to_float((e & 1) ? (pair >> 16) : (pair & 0xffffu));
+}
+
+// Split-K accumulator word: bits 63..10 = sum of the slices' partials in units of
+// 2^-34 (two's complement, wraps modulo 2^54), bits 9..0 = number of slices that
+// have arrived.  A slice adds (fixed << 10) + 1.
+constexpr int kCountBits = 10;
+constexpr double kFixedScale = 17179869184.0;  // 2^34
+
+__device__ __forceinline__ unsigned long long encode_partial(float v)
+{
+    // keep the conversion in range; magnitudes this large cannot end in a finite binary16
+    v = fminf(fmaxf(v, -536870848.0f), 536870848.0f);  // |v| < 2^29
+    long long fixed = __double2ll_rn(static_cast<double>(v) * kFixedScale);  // exact product
+    return (static_cast<unsigned long long>(fixed) << kCountBits) + 1ull;
+}
+
+// Value of a completed accumulator word (arrival count dropped).
+__device__ __forceinline__ float decode_total(unsigned long long total)
+{
+    const long long fixed = static_cast<long long>(total) >> kCountBits;
+    return static_cast<float>(static_cast<double>(fixed) * (1.0 / kFixedScale));
+}
+
+__device__ __forceinline__ unsigned arrivals_of(unsigned long long total)
+{
+    return static_cast<unsigned>(total) & ((1u << kCountBits) - 1u);
+}
+
+}  // namespace bcq
