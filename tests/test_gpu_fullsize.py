@@ -48,3 +48,10 @@ def test_opt66b_q3_outliers():
 def test_llama70b_shapes(M, N, q):
     """configs[4]: GQA k/v projection and the down projection"""
     _check(M, N, q, False)
+
+
+@pytest.mark.parametrize("M,N,q,offset,batch", [(7168, 7168, 2, True, 8), (9216, 9216, 3, False, 4),
+                                                  (9216, 9216, 3, False, 16), (28672, 7168, 2, True, 8)])
+def test_skinny_fullsize(M, N, q, offset, batch):
+    """configs[2] (q=2 with offset, batch 8) and configs[3] (batch 4 and 16, outlier channels)"""
+    _check(M, N, q, offset, batch=batch, outlier_frac=0.01 if M == 9216 else 0.0)

@@ -140,3 +140,36 @@ def test_skinny_strided_rows():
 def test_outlier_channels():
     """configs[3] activation recipe: 1% of channels scaled x20."""
     _run_case(512, 9216, 3, 128, False, seed=3, outlier_frac=0.01)
+
+
+@pytest.mark.parametrize("parts", [1, 2, 3, 7])
+def test_skinny_k_split_does_not_change_results(parts):
+    """The K split of the skinny kernel only changes how partial sums are grouped; on exact
+    inputs every split must give the oracle's result bit for bit."""
+    L = bcq_synth.make_exact_layer(200, 3584, 3, group=128, offset=True, batch=5, seed=12)
+    pl = U.upload_and_pack(L, max_batch=5)
+    try:
+        bcq.set_option("skinny_parts", parts)
+        Y = U.gpu_gemm(pl, U.x_dev(L)).astype(np.float64)
+    finally:
+        bcq.set_option("skinny_parts", 0)
+    # every partial sum is exact in fp32 and in the fixed-point accumulator, so the only
+    # rounding is the final one to binary16 (round to nearest even, as numpy does)
+    y_ref = ref.gemm(L.planes, L.alpha, L.offset, L.x)
+    assert np.abs(y_ref).max() < 2 ** 14
+    assert np.array_equal(Y, y_ref.astype(np.float16).astype(np.float64))
+    assert not pl.workspace.cpu().numpy().any()
+
+
+def test_skinny_negative_alpha_and_ragged():
+    """alpha of either sign (the sign is folded into the plane bits), M % 32 != 0, N % 512 != 0."""
+    L = bcq_synth.make_layer(77, 1120, 3, group=1120, offset=True, batch=3, seed=8)
+    a = L.alpha.copy()
+    a[::2, :, 1] = -a[::2, :, 1]
+    a[1::3, :, 0] = -a[1::3, :, 0]
+    L.alpha = a
+    pl = U.upload_and_pack(L, max_batch=3)
+    U.gate(U.gpu_gemm(pl, U.x_dev(L)), ref.gemm(L.planes, L.alpha, L.offset, L.x))
+    # the batch-1 kernel on the same layer
+    y1 = U.gpu_gemv(pl, U.x_dev(L))
+    U.gate(y1[None, :], ref.gemm(L.planes, L.alpha, L.offset, L.x[:1]))
