@@ -1,13 +1,18 @@
 #!/usr/bin/env python3
 """Benchmark of the binary-coding GEMV (inference path of GPTQT) on one MI355X.
 
-Workload (benchmark configs[1]): the OPT-30B-shaped 3-bit layer set at
+Default workload (benchmark configs[1]): the OPT-30B-shaped 3-bit layer set at
 batch 1 -- 7168x7168 (attention projection), 28672x7168 (fc1), 7168x28672 (fc2),
 q = 3, group 128, no offset, synthetic seeded inputs (bcq_synth).  One "step" is
-one pass over the three layers, one bcq_gemv each, on one stream.  Weights are
+one pass over the layers, one bcq_gemv each, on one stream.  Weights are
 resident in HBM before timing; every step reads a different copy of the packed
 weights (the copies total > 1 GiB) so that neither L2 nor the 256 MB memory-side
 cache serves them.
+
+Other workloads (--workload): `llama70b_block` = configs[4], the seven GEMVs of a
+Llama-2-70B-shaped decoder block in sequence; `llama70b_block_fused` = the same
+weights with the projections that share their input (q/k/v; gate/up) packed into
+one blob each with bcq_pack_rows, four GEMVs per step.  --q selects 2 or 3 planes.
 
 Prints ONE JSON line (see README for the fields).  `value` is the
 effective weight bandwidth of the whole step; `roofline` is for the dominant
@@ -25,9 +30,22 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X published peak
-LAYERS = [("attn_proj", 7168, 7168), ("fc1", 28672, 7168), ("fc2", 7168, 28672)]
-DOMINANT = "fc2"
-Q, GROUP = 3, 128
+GROUP = 128
+# name -> (launches, dominant launch, description); a launch = (name, [(part name, rows), ...], N)
+WORKLOADS = {
+    "opt30b": ([("attn_proj", [("attn_proj", 7168)], 7168), ("fc1", [("fc1", 28672)], 7168),
+                ("fc2", [("fc2", 7168)], 28672)], "fc2",
+               "OPT-30B-shaped layer set (7168x7168, 28672x7168, 7168x28672)"),
+    "llama70b_block": ([("q", [("q", 8192)], 8192), ("k", [("k", 1024)], 8192), ("v", [("v", 1024)], 8192),
+                        ("o", [("o", 8192)], 8192), ("gate", [("gate", 28672)], 8192),
+                        ("up", [("up", 28672)], 8192), ("down", [("down", 8192)], 28672)], "down",
+                       "Llama-2-70B-shaped decoder block, 7 GEMVs in sequence (q, k, v, o, gate, up, down)"),
+    "llama70b_block_fused": ([("qkv", [("q", 8192), ("k", 1024), ("v", 1024)], 8192), ("o", [("o", 8192)], 8192),
+                              ("gate_up", [("gate", 28672), ("up", 28672)], 8192),
+                              ("down", [("down", 8192)], 28672)], "down",
+                             "Llama-2-70B-shaped decoder block, 4 GEMVs in sequence (q/k/v and gate/up share "
+                             "their input and are packed row-wise into one blob each)"),
+}
 PAPER_CONTEXT = ("paper Table IV: GPTQT 3-bit is 1.24x faster than GPTQ 3-bit (and 3.4x faster than fp16) on "
                  "opt-30b, batch 1, NVIDIA RTX A5000, 128-token generation; no per-GEMV time or GB/s is published")
 
@@ -37,6 +55,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=60)
     ap.add_argument("--warmup", type=int, default=12)
+    ap.add_argument("--workload", choices=sorted(WORKLOADS), default="opt30b")
+    ap.add_argument("--q", type=int, choices=(2, 3), default=3, help="number of sign planes")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -63,21 +83,31 @@ def main():
     def to_dev(a):
         return torch.from_numpy(np.ascontiguousarray(a)).to(dev)
 
+    LAUNCHES, DOMINANT, WORKLOAD_TEXT = WORKLOADS[args.workload]
+    LAYERS = [(name, sum(rows for _, rows in parts), N) for name, parts, N in LAUNCHES]
+    Q = args.q
+
     # ---- build and pack the layer set (not timed) ------------------------------
     layers = {}
     total_bytes = 0
-    for name, M, N in LAYERS:
-        L = bcq_synth.make_layer(M, N, Q, group=GROUP, offset=False, batch=1, seed=0)
+    for name, parts, N in LAUNCHES:
+        M = sum(rows for _, rows in parts)
         pl = bcq.PackedLayer(M, N, Q, GROUP, False)
-        codes = to_dev(L.codes())
-        alpha = to_dev(L.alpha.view(np.uint16).astype(np.int16)).view(torch.float16)
-        pl.pack_from(codes, alpha, None)
-        torch.cuda.synchronize()
-        del codes
-        x = to_dev(L.x.view(np.uint16).astype(np.int16)).view(torch.float16)[0]
+        subs, row0, nbytes = [], 0, 0
+        for k, (pname, rows) in enumerate(parts):  # each projection from its own tensors
+            L = bcq_synth.make_layer(rows, N, Q, group=GROUP, offset=False, batch=1, seed=k)
+            codes = to_dev(L.codes())
+            alpha = to_dev(L.alpha.view(np.uint16).astype(np.int16)).view(torch.float16)
+            pl.pack_rows_from(row0, codes, alpha, None)
+            torch.cuda.synchronize()
+            del codes, alpha
+            subs.append((row0, L))
+            row0 += rows
+            nbytes += L.weight_bytes()
+        x = to_dev(subs[0][1].x.view(np.uint16).astype(np.int16)).view(torch.float16)[0]
         y = torch.empty(M, dtype=torch.float16, device=dev)
-        layers[name] = dict(L=L, pl=pl, x=x, y=y, bytes=L.weight_bytes(), copies=[pl.packed])
-        total_bytes += L.weight_bytes()
+        layers[name] = dict(subs=subs, pl=pl, x=x, y=y, bytes=nbytes, copies=[pl.packed])
+        total_bytes += nbytes
     n_copies = max(2, math.ceil(1.25 * 2 ** 30 / total_bytes))
     for name in layers:
         ent = layers[name]
@@ -147,12 +177,13 @@ def main():
                                pct_of_hbm_peak=round(layers[name]["bytes"] / us / 1e3 / HBM_PEAK_GBS * 100, 2))
     dom = per_layer[DOMINANT]
     achieved = dom["weight_bytes"] / (dom["us_per_gemv"] * 1e-6) / 1e9
-    roofline = dict(bound="hbm", kernel="bcq_gemv_kernel<3,0,4> on 7168x28672", achieved=round(achieved, 1),
+    roofline = dict(bound="hbm", kernel="bcq_gemv_kernel (q=%d, no offset, group 128) on %dx%d" % (Q, dom["M"], dom["N"]),
+                    achieved=round(achieved, 1),
                     peak=HBM_PEAK_GBS, unit="GB/s", frac=round(achieved / HBM_PEAK_GBS, 4),
                     bytes_per_launch=dom["weight_bytes"], us_per_launch=dom["us_per_gemv"], traffic=None)
     # HBM bytes per launch measured separately with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE); see profiles/
     traffic_file = os.path.join(ROOT, "profiles", "bcq_gemv_opt30b_q3_hbm_traffic.md")
-    if os.path.exists(traffic_file):
+    if os.path.exists(traffic_file) and args.workload == "opt30b" and Q == 3:
         for line in open(traffic_file):
             if line.startswith("hbm_bytes_per_launch_fc2"):
                 roofline["traffic"] = float(line.split("=")[1])
@@ -165,25 +196,27 @@ def main():
         t0 = time.perf_counter()
         worst = 0.0
         for name, M, N in LAYERS:
-            L = layers[name]["L"]
-            y_ref = ref.gemm(L.planes, L.alpha, None, L.x)[0]
-            y_gpu = layers[name]["y"].cpu().numpy().astype(np.float64)
-            rms = math.sqrt(float(np.mean(y_ref ** 2)))
-            err = np.abs(y_gpu - y_ref) / np.maximum(np.abs(y_ref), rms / 64.0)
-            worst = max(worst, float(err.max()))
+            x0 = layers[name]["subs"][0][1].x  # the activations every part of this launch was given
+            y_all = layers[name]["y"].cpu().numpy().astype(np.float64)
+            for row0, L in layers[name]["subs"]:
+                y_ref = ref.gemm(L.planes, L.alpha, None, x0)[0]
+                y_gpu = y_all[row0:row0 + L.M]
+                rms = math.sqrt(float(np.mean(y_ref ** 2)))
+                err = np.abs(y_gpu - y_ref) / np.maximum(np.abs(y_ref), rms / 64.0)
+                worst = max(worst, float(err.max()))
         t_cpu = time.perf_counter() - t0
         cpu = dict(value=round(total_bytes / t_cpu / 1e9, 4), unit="GB/s", cores=ref.num_threads(), kind="oracle",
-                   sample="full layer set, one pass (all rows of the 3 layers), fp64 dequant + matvec",
+                   sample="full layer set, one pass (all rows of every layer), fp64 dequant + matvec",
                    seconds=round(t_cpu, 2))
         parity = dict(max_gated_rel_err=worst, tolerance=2e-3)
 
     out = {
-        "metric": "effective weight GB/s (and us per GEMV), 3-bit batch-1 binary-coding GEMV",
+        "metric": "effective weight GB/s (and us per GEMV), %d-bit batch-1 binary-coding GEMV" % Q,
         "value": round(value_gbs, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f16 activations, 1-bit planes x3, f32 accumulate", "data": "synthetic",
-        "config": {"workload": "OPT-30B-shaped layer set (7168x7168, 28672x7168, 7168x28672), q=3, group=128, "
-                               "batch=1, cold weights (%d rotating copies)" % n_copies,
+        "dtype": "f16 activations, 1-bit planes x%d, f32 accumulate" % Q, "data": "synthetic",
+        "config": {"workload": "%s, q=%d, group=128, batch=1, cold weights (%d rotating copies)"
+                               % (WORKLOAD_TEXT, Q, n_copies), "launches_per_step": len(LAYERS),
                    "weight_bytes_per_step": total_bytes, "launch": "graph" if not args.no_graph else "eager"},
         "pct_of_hbm_peak": round(value_gbs / HBM_PEAK_GBS * 100, 2),
         "layers": per_layer, "roofline": roofline, "cpu_baseline": cpu, "parity": parity,

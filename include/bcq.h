@@ -54,10 +54,10 @@ typedef enum {
  *               523776 (larger N is BCQ_ERR_UNSUPPORTED)
  *   q           number of sign planes, 1..4 (the paper uses 2 and 3)
  *   group       columns sharing one alpha per plane (and one offset); must
- *               divide N and be a multiple of 128 or N itself (any N).
+ *               divide N and be 32, 64, a multiple of 128, or N itself (any N).
  *               group == N gives the paper's row-wise parameters (Sec. II-A:
  *               quantisation parameters are fixed per row).  Other multiples
- *               of 32 are well-formed but BCQ_ERR_UNSUPPORTED.
+ *               of 32 (96, 160, ...) are well-formed but BCQ_ERR_UNSUPPORTED.
  *   has_offset  1 if the fused offset term of Eq. 11, (2^n-1)/2*S + qbias, is
  *               present, else 0
  *   layout_version  set by bcq_pack; bcq_gemv / bcq_gemm_skinny / bcq_unpack
@@ -103,6 +103,21 @@ bcq_status bcq_workspace_init(void *workspace, size_t bytes, void *stream);
  */
 bcq_status bcq_pack(bcq_desc *desc, const uint8_t *codes, const uint16_t *alpha,
                     const uint16_t *offset, void *packed, void *stream);
+
+/*
+ * bcq_pack for a range of rows: writes the rows [row_begin, row_begin + rows) of the layer
+ * `desc` describes from sources that hold ONLY those rows (codes [rows][N], alpha
+ * [rows][N/group][q], offset [rows][N/group]).  Layers that are applied to the same
+ * activations (the q/k/v projections of an attention block, the gate/up projections of a
+ * gated MLP) can so be packed from their own tensors into one blob with M = the sum of their
+ * rows, and then cost ONE bcq_gemv / bcq_gemm_skinny: one launch, one staging of the
+ * activations, y = the concatenation of their outputs (Eq. 11 is row-wise, so stacking rows
+ * changes no result).  Every row of the layer must be covered by some call before the blob is
+ * used; the call that covers the last row also writes the padding.  Calls for disjoint row
+ * ranges may run concurrently.  Sets desc->layout_version.
+ */
+bcq_status bcq_pack_rows(bcq_desc *desc, int32_t row_begin, int32_t rows, const uint8_t *codes,
+                         const uint16_t *alpha, const uint16_t *offset, void *packed, void *stream);
 
 /* Inverse of bcq_pack (for tests): any of codes / alpha / offset may be NULL
  * to skip that output.  All DEVICE. */

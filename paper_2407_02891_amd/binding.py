@@ -13,7 +13,7 @@ BCQ_LAYOUT_VERSION = 1
 BCQ_MAX_BATCH = 16
 
 EXPORTS = ["bcq_packed_bytes", "bcq_workspace_bytes", "bcq_workspace_init", "bcq_pack",
-           "bcq_unpack", "bcq_gemv", "bcq_gemm_skinny", "bcq_read_probe_sink_bytes",
+           "bcq_pack_rows", "bcq_unpack", "bcq_gemv", "bcq_gemm_skinny", "bcq_read_probe_sink_bytes",
            "bcq_read_probe", "bcq_set_option", "bcq_status_string"]
 
 
@@ -47,6 +47,7 @@ def lib():
         L.bcq_workspace_bytes.restype, L.bcq_workspace_bytes.argtypes = sz, [dp, i32]
         L.bcq_workspace_init.restype, L.bcq_workspace_init.argtypes = i32, [vp, sz, vp]
         L.bcq_pack.restype, L.bcq_pack.argtypes = i32, [dp, vp, vp, vp, vp, vp]
+        L.bcq_pack_rows.restype, L.bcq_pack_rows.argtypes = i32, [dp, i32, i32, vp, vp, vp, vp, vp]
         L.bcq_unpack.restype, L.bcq_unpack.argtypes = i32, [dp, vp, vp, vp, vp, vp]
         L.bcq_gemv.restype, L.bcq_gemv.argtypes = i32, [dp, vp, vp, vp, vp, vp]
         L.bcq_gemm_skinny.restype = i32
@@ -105,6 +106,11 @@ def pack(desc, codes, alpha, offset, packed, stream=None):
                           _stream(stream)), "bcq_pack")
 
 
+def pack_rows(desc, row_begin, rows, codes, alpha, offset, packed, stream=None):
+    _check(lib().bcq_pack_rows(ctypes.byref(desc), int(row_begin), int(rows), _ptr(codes), _ptr(alpha),
+                               _ptr(offset), _ptr(packed), _stream(stream)), "bcq_pack_rows")
+
+
 def unpack(desc, packed, codes, alpha, offset, stream=None):
     _check(lib().bcq_unpack(ctypes.byref(desc), _ptr(packed), _ptr(codes), _ptr(alpha), _ptr(offset),
                             _stream(stream)), "bcq_unpack")
@@ -153,6 +159,11 @@ class PackedLayer:
     def pack_from(self, codes, alpha, offset):
         """codes uint8 [M][N], alpha fp16 [M][G][q], offset fp16 [M][G] or None (device tensors)."""
         pack(self.desc, codes, alpha, offset, self.packed)
+        return self
+
+    def pack_rows_from(self, row_begin, codes, alpha, offset):
+        """Rows [row_begin, row_begin + codes.shape[0]) from tensors that hold only those rows."""
+        pack_rows(self.desc, row_begin, codes.shape[0], codes, alpha, offset, self.packed)
         return self
 
     def gemv(self, x, y=None):

@@ -1,6 +1,7 @@
 """Build libbcq.so (HIP, gfx950 only) in-tree with hipcc."""
 import glob
 import os
+import re
 import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
@@ -19,12 +20,56 @@ def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
 
+def kernel_resources(stderr_text):
+    """Parse the compiler's kernel-resource-usage remarks: {mangled name: {field: int}}."""
+    res, cur = {}, None
+    for line in stderr_text.splitlines():
+        m = re.search(r"remark:\s+Function Name: (\S+)", line)
+        if m:
+            cur = res.setdefault(m.group(1), {})
+            continue
+        m = re.search(r"remark:\s+([A-Za-z ]+?)(?: \[[^\]]*\])?: (\d+) \[-Rpass", line)
+        if m and cur is not None:
+            cur[m.group(1).strip()] = int(m.group(2))
+    return res
+
+
 def build(verbose=False, extra_flags=()):
+    """Compile every kernel for gfx950 and link libbcq.so.  Fails if a compute kernel (GEMV,
+    skinny GEMM) needs scratch memory or spills registers: those kernels are sized to keep
+    everything in registers, and a spill would silently cost HBM traffic."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + HIPCC_FLAGS + list(extra_flags) + sources() + ["-o", LIB]
+    cmd = [hipcc] + HIPCC_FLAGS + ["-Rpass-analysis=kernel-resource-usage"] + list(extra_flags) + sources() \
+        + ["-o", LIB]
     if verbose:
         print(" ".join(cmd))
-    subprocess.run(cmd, check=True)
+    proc = subprocess.run(cmd, stderr=subprocess.PIPE, text=True)
+    noise = ("-Rpass-analysis=kernel-resource-usage", "packed-fp32-ops", "warning generated", "warnings generated")
+    other, skip = [], 0
+    for line in proc.stderr.splitlines():
+        if skip:  # the two source-excerpt lines that follow a located remark
+            skip -= 1
+            if re.match(r"\s+\d* *\|", line):
+                continue
+        if any(n in line for n in noise):
+            skip = 2 if "Function Name" in line else 0
+            continue
+        other.append(line)
+    if other:
+        print("\n".join(other))
+    if proc.returncode != 0:
+        raise subprocess.CalledProcessError(proc.returncode, cmd)
+    res = kernel_resources(proc.stderr)
+    hot = {k: v for k, v in res.items() if "bcq_gemv_kernel" in k or "bcq_skinny_kernel" in k}
+    if not hot:
+        raise RuntimeError("no resource remarks for the compute kernels: cannot check for spills")
+    bad = {k: v for k, v in hot.items()
+           if v.get("ScratchSize", 0) or v.get("VGPRs Spill", 0) or v.get("SGPRs Spill", 0)}
+    if bad:
+        raise RuntimeError(f"compute kernels use scratch or spill registers: {bad}")
+    if verbose:
+        for k, v in sorted(hot.items()):
+            print(f"{k}: VGPRs {v.get('VGPRs')} AGPRs {v.get('AGPRs')} occupancy {v.get('Occupancy')}")
     return LIB
 
 

@@ -20,8 +20,7 @@ bool desc_ok(const bcq_desc *d, bcq_status *why)
     *why = BCQ_ERR_UNSUPPORTED;
     if (d->q > kMaxQ) return false;
     const bool one_scale_per_block = d->group % 128 == 0 || d->group == d->N;
-    if (!(one_scale_per_block || d->group == 32 || d->group == 64)) return false;
-    if (!one_scale_per_block) return false;  // groups of 32/64: laid out by bcq_pack, not yet computed by the GEMV
+    if (!(one_scale_per_block || d->group == 32 || d->group == 64)) return false;  // e.g. 96, 160
     if (((long long)d->N + kTileCols - 1) / kTileCols > kMaxSlices) return false;  // split-K arrival count is 10 bits
     // blob offsets are size_t; tile counts must fit int
     if ((long long)d->M + kTileRows > 0x7fffffffLL || (long long)d->N + kTileCols > 0x7fffffffLL) return false;
@@ -65,18 +64,27 @@ bcq_status bcq_workspace_init(void *workspace, size_t bytes, void *stream)
                                                                                              : BCQ_ERR_HIP;
 }
 
-bcq_status bcq_pack(bcq_desc *desc, const uint8_t *codes, const uint16_t *alpha, const uint16_t *offset,
-                    void *packed, void *stream)
+bcq_status bcq_pack_rows(bcq_desc *desc, int32_t row_begin, int32_t rows, const uint8_t *codes,
+                         const uint16_t *alpha, const uint16_t *offset, void *packed, void *stream)
 {
     bcq_status why;
     if (!desc_ok(desc, &why)) return why;
+    if (row_begin < 0 || rows <= 0 || (long long)row_begin + rows > desc->M) return BCQ_ERR_INVALID_ARG;
     if (!codes || !alpha || !packed) return BCQ_ERR_INVALID_ARG;
     if ((desc->has_offset != 0) != (offset != nullptr)) return BCQ_ERR_INVALID_ARG;
     if (!aligned(packed, 256) || !aligned(alpha, 2) || (offset && !aligned(offset, 2))) return BCQ_ERR_INVALID_ARG;
-    if (launch_pack(geom_of(desc), codes, alpha, offset, packed, static_cast<hipStream_t>(stream)) != hipSuccess)
+    if (launch_pack(geom_of(desc), row_begin, rows, codes, alpha, offset, packed,
+                    static_cast<hipStream_t>(stream)) != hipSuccess)
         return BCQ_ERR_HIP;
     desc->layout_version = BCQ_LAYOUT_VERSION;
     return BCQ_OK;
+}
+
+bcq_status bcq_pack(bcq_desc *desc, const uint8_t *codes, const uint16_t *alpha, const uint16_t *offset,
+                    void *packed, void *stream)
+{
+    if (!desc) return BCQ_ERR_INVALID_ARG;
+    return bcq_pack_rows(desc, 0, desc->M, codes, alpha, offset, packed, stream);
 }
 
 bcq_status bcq_unpack(const bcq_desc *desc, const void *packed, uint8_t *codes, uint16_t *alpha,

@@ -19,31 +19,39 @@ __device__ __forceinline__ uint16_t float_to_half_bits(float v)
     return __builtin_bit_cast(uint16_t, static_cast<_Float16>(v));  // round to nearest even
 }
 
-template <int Q, int Z>
+// One tile's share of a lane.  SUB = scaling groups per 128-column block (1, 2 or 4).
+template <int Q, int Z, int SUB = 1>
 struct TileRegs {
     u32x4 planes[2][Q];
-    uint32_t scales[Q + Z];  // binary16 pairs: [t][c] flattened, 2*(Q+Z) halves
+    uint32_t scales[(Q + Z) * SUB];  // binary16 pairs: [t][range][c] flattened, 2*SUB*(Q+Z) halves
 };
 
-template <int Q, int Z>
-__device__ __forceinline__ void load_tile(TileRegs<Q, Z> &r, const uint8_t *tile, int lane)
+template <int Q, int Z, int SUB>
+__device__ __forceinline__ void load_tile(TileRegs<Q, Z, SUB> &r, const uint8_t *tile, int lane)
 {
     const u32x4 *pp = reinterpret_cast<const u32x4 *>(tile) + lane;
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
         for (int i = 0; i < Q; ++i) r.planes[t][i] = __builtin_nontemporal_load(pp + (t * Q + i) * 64);
-    const uint32_t *sp = reinterpret_cast<const uint32_t *>(tile + 2u * Q * 1024u) + lane * (Q + Z);
+    const uint32_t *sp = reinterpret_cast<const uint32_t *>(tile + 2u * Q * 1024u) + lane * ((Q + Z) * SUB);
 #pragma unroll
-    for (int c = 0; c < Q + Z; ++c) r.scales[c] = __builtin_nontemporal_load(sp + c);
+    for (int c = 0; c < (Q + Z) * SUB; ++c) r.scales[c] = __builtin_nontemporal_load(sp + c);
 }
 
-template <int Q, int Z>
-__device__ __forceinline__ float scale_of(const TileRegs<Q, Z> &r, int t, int c)
+// binary16 bits of scale c (alpha_0..alpha_{Q-1}, then the offset) of row half t, byte range `range`
+template <int Q, int Z, int SUB>
+__device__ __forceinline__ uint32_t scale_bits_of(const TileRegs<Q, Z, SUB> &r, int t, int range, int c)
 {
-    int e = t * (Q + Z) + c;  // half index
-    uint32_t pair = r.scales[e >> 1];
-    return half_bits_to_float((e & 1) ? (pair >> 16) : (pair & 0xffffu));
+    const int e = (t * SUB + range) * (Q + Z) + c;  // half index
+    const uint32_t pair = r.scales[e >> 1];
+    return (e & 1) ? (pair >> 16) : (pair & 0xffffu);
+}
+
+template <int Q, int Z, int SUB>
+__device__ __forceinline__ float scale_of(const TileRegs<Q, Z, SUB> &r, int t, int range, int c)
+{
+    return half_bits_to_float(scale_bits_of<Q, Z, SUB>(r, t, range, c));
 }
 
 // Split-K accumulator word: bits 63..10 = sum of the slices' partials in units of

@@ -36,7 +36,11 @@
 //  * The grid is exactly as large as the chip holds at once (two 64 KB-LDS
 //    workgroups on each of the 256 CUs) whenever the problem is big enough, with
 //    the column slices cut into unequal numbers of row parts to get there, so all
-//    CUs carry the same load.
+//    CUs carry the same load.  Workgroups have 8 waves (16 per CU) when every
+//    wave still gets a tile, else 4.
+//  * When a 128-column block holds several scaling groups (group 32 or 64) the
+//    blob keeps each group in a fixed byte range of the lane's 16 bytes
+//    (bcq_layout.h), so a lane sums its lookups per range and applies one alpha each.
 #include "bcq_internal.h"
 #include "bcq_device.h"
 
@@ -77,25 +81,26 @@ __device__ __forceinline__ float lookup(const float *lut, uint32_t w, uint32_t r
     return *reinterpret_cast<const float *>(reinterpret_cast<const char *>(lut) + addr);
 }
 
-__device__ __forceinline__ float sign_sum16(const float *lut, const u32x4 &p, const uint32_t (&rv)[4])
+// The 16 lookups of one (row, block, plane), summed per byte range: s[p] is the sign sum of
+// the lane's bytes [16/SUB * p, 16/SUB * (p + 1)), i.e. of one scaling group.
+template <int SUB>
+__device__ __forceinline__ void sign_sums(const float *lut, const u32x4 &p, const uint32_t (&rv)[4], float (&s)[SUB])
 {
-    float s = lookup<0>(lut, p.x, rv[0]);
-    s += lookup<1>(lut, p.x, rv[0]);
-    s += lookup<2>(lut, p.x, rv[0]);
-    s += lookup<3>(lut, p.x, rv[0]);
-    s += lookup<0>(lut, p.y, rv[1]);
-    s += lookup<1>(lut, p.y, rv[1]);
-    s += lookup<2>(lut, p.y, rv[1]);
-    s += lookup<3>(lut, p.y, rv[1]);
-    s += lookup<0>(lut, p.z, rv[2]);
-    s += lookup<1>(lut, p.z, rv[2]);
-    s += lookup<2>(lut, p.z, rv[2]);
-    s += lookup<3>(lut, p.z, rv[2]);
-    s += lookup<0>(lut, p.w, rv[3]);
-    s += lookup<1>(lut, p.w, rv[3]);
-    s += lookup<2>(lut, p.w, rv[3]);
-    s += lookup<3>(lut, p.w, rv[3]);
-    return s;
+    float d[4];
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+        float a = lookup<0>(lut, p[v], rv[v]);
+        a += lookup<1>(lut, p[v], rv[v]);
+        a += lookup<2>(lut, p[v], rv[v]);
+        a += lookup<3>(lut, p[v], rv[v]);
+        d[v] = a;
+    }
+    if (SUB == 1) s[0] = (d[0] + d[1]) + (d[2] + d[3]);
+    if (SUB == 2) { s[0] = d[0] + d[1]; s[SUB - 1] = d[2] + d[3]; }
+    if (SUB == 4) {
+#pragma unroll
+        for (int v = 0; v < 4; ++v) s[v % SUB] = d[v];
+    }
 }
 
 // Completes one row: `total` is the accumulator word after this slice's add.  The
@@ -109,7 +114,7 @@ __device__ __forceinline__ void complete_row(const GemvParams &p, int row, unsig
     }
 }
 
-template <int Q, int Z, int NW>
+template <int Q, int Z, int NW, int SUB>
 __global__ __launch_bounds__(NW * 64) void bcq_gemv_kernel(GemvParams p)
 {
     __shared__ float lut[256 * 64];  // 64 KB: entry idx of chunk c at lut[idx*64 + c]
@@ -141,11 +146,11 @@ __global__ __launch_bounds__(NW * 64) void bcq_gemv_kernel(GemvParams p)
     const uint8_t *tile_ptr = p.blob + ((size_t)slice * p.ntile + t_begin) * p.tile_bytes;
 
     // Start the first tile's loads before building the tables.
-    TileRegs<Q, Z> cur;
+    TileRegs<Q, Z, SUB> cur;
     const int col0 = slice * kTileCols + kChunkCols * lane;  // lane = chunk
     u32x4 xr = {0u, 0u, 0u, 0u};
     if (col0 < p.N) xr = *reinterpret_cast<const u32x4 *>(p.x + col0);
-    if (t_begin < t_end) load_tile<Q, Z>(cur, tile_ptr, lane);
+    if (t_begin < t_end) load_tile<Q, Z, SUB>(cur, tile_ptr, lane);
 
     // ---- sign-sum tables for the 512 activations of this slice ----------------
     {
@@ -186,13 +191,18 @@ __global__ __launch_bounds__(NW * 64) void bcq_gemv_kernel(GemvParams p)
     for (int v = 0; v < 4; ++v) {
         uint32_t w = 0;
 #pragma unroll
-        for (int n = 0; n < 4; ++n) w |= (uint32_t)(4 * (16 * h + ((4 * v + n + r) & 15))) << (8 * n);
+        for (int n = 0; n < 4; ++n) w |= (uint32_t)(4 * (16 * h + chunk_of_byte(4 * v + n, r, SUB))) << (8 * n);
         rv[v] = w;
     }
-    float xsum = 0.0f;  // sum of the activations of this lane's 128-column block
-    if (Z) {
+    float xsum[SUB];  // sums of the activations of this lane's block, per byte range (scaling group)
 #pragma unroll
-        for (int c = 0; c < 16; ++c) xsum += lut[255 * 64 + 16 * h + c];
+    for (int g = 0; g < SUB; ++g) {
+        xsum[g] = 0.0f;
+        if (Z) {
+            const int c0 = (16 / SUB) * subgroup_of_range(g, r, SUB);
+#pragma unroll
+            for (int c = 0; c < 16 / SUB; ++c) xsum[g] += lut[255 * 64 + 16 * h + c0 + c];
+        }
     }
 
     // ---- stream the row tiles ----------------------------------------------------
@@ -222,18 +232,25 @@ __global__ __launch_bounds__(NW * 64) void bcq_gemv_kernel(GemvParams p)
                                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
-        TileRegs<Q, Z> nxt;
+        TileRegs<Q, Z, SUB> nxt;
         tile_ptr += p.tile_bytes;
-        if (tile + 1 < t_end) load_tile<Q, Z>(nxt, tile_ptr, lane);  // (d)
+        if (tile + 1 < t_end) load_tile<Q, Z, SUB>(nxt, tile_ptr, lane);  // (d)
 
         float acc[2];  // (e)
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
             float a = 0.0f;
 #pragma unroll
-            for (int i = 0; i < Q; ++i)
-                a = fmaf(scale_of<Q, Z>(cur, t, i), sign_sum16(lut, cur.planes[t][i], rv), a);
-            if (Z) a = fmaf(scale_of<Q, Z>(cur, t, Q), xsum, a);
+            for (int i = 0; i < Q; ++i) {
+                float ss[SUB];
+                sign_sums<SUB>(lut, cur.planes[t][i], rv, ss);
+#pragma unroll
+                for (int g = 0; g < SUB; ++g) a = fmaf(scale_of<Q, Z, SUB>(cur, t, g, i), ss[g], a);
+            }
+            if (Z) {
+#pragma unroll
+                for (int g = 0; g < SUB; ++g) a = fmaf(scale_of<Q, Z, SUB>(cur, t, g, Q), xsum[g], a);
+            }
             // sum the four block owners (lanes r, r+16, r+32, r+48) of each row
             a += __shfl_xor(a, 16, 64);
             a += __shfl_xor(a, 32, 64);
@@ -281,24 +298,30 @@ int auto_workgroups(const Geom &g, int waves_per_group)
     return (int)groups;
 }
 
-template <int Q, int Z, int NW>
+template <int Q, int Z, int NW, int SUB>
 static hipError_t launch_one(const GemvParams &p, int groups, hipStream_t stream)
 {
-    hipLaunchKernelGGL((bcq_gemv_kernel<Q, Z, NW>), dim3((unsigned)groups), dim3(NW * 64), 0,
+    hipLaunchKernelGGL((bcq_gemv_kernel<Q, Z, NW, SUB>), dim3((unsigned)groups), dim3(NW * 64), 0,
                        stream, p);
     return hipGetLastError();
 }
 
 template <int Q, int Z>
-static hipError_t launch_qz(const GemvParams &p, const GemvTuning &t, int groups, hipStream_t stream)
+static hipError_t launch_qz(const GemvParams &p, int waves, int sub, int groups, hipStream_t stream)
 {
-    return t.waves == 8 ? launch_one<Q, Z, 8>(p, groups, stream) : launch_one<Q, Z, 4>(p, groups, stream);
+    if (sub == 2) return launch_one<Q, Z, 4, 2>(p, groups, stream);
+    if (sub == 4) return launch_one<Q, Z, 4, 4>(p, groups, stream);
+    return waves == 8 ? launch_one<Q, Z, 8, 1>(p, groups, stream) : launch_one<Q, Z, 4, 1>(p, groups, stream);
 }
 
 hipError_t launch_gemv(const Geom &g, const void *packed, const uint16_t *x, uint16_t *y,
                        void *workspace, const GemvTuning &t, hipStream_t stream)
 {
-    const int nw = t.waves == 8 ? 8 : 4;
+    // 8 waves per workgroup (16 per CU) hide latency better once every wave still gets a tile;
+    // the variants with several scaling groups per block exist with 4 waves only
+    const long long tiles = (long long)g.nslice * g.ntile;
+    const int want = t.waves ? t.waves : (tiles >= 8LL * kResidentGroups ? 8 : 4);
+    const int nw = (want == 8 && g.sub == 1) ? 8 : 4;
     int groups = t.workgroups > 0 ? t.workgroups : auto_workgroups(g, nw);
     // at least one workgroup per slice, at most one per row tile of a slice
     if (groups < g.nslice) groups = g.nslice;
@@ -318,14 +341,14 @@ hipError_t launch_gemv(const Geom &g, const void *packed, const uint16_t *x, uin
 #endif
     const int key = g.q * 2 + g.z;
     switch (key) {
-        case 2: return launch_qz<1, 0>(p, t, groups, stream);
-        case 3: return launch_qz<1, 1>(p, t, groups, stream);
-        case 4: return launch_qz<2, 0>(p, t, groups, stream);
-        case 5: return launch_qz<2, 1>(p, t, groups, stream);
-        case 6: return launch_qz<3, 0>(p, t, groups, stream);
-        case 7: return launch_qz<3, 1>(p, t, groups, stream);
-        case 8: return launch_qz<4, 0>(p, t, groups, stream);
-        case 9: return launch_qz<4, 1>(p, t, groups, stream);
+        case 2: return launch_qz<1, 0>(p, nw, g.sub, groups, stream);
+        case 3: return launch_qz<1, 1>(p, nw, g.sub, groups, stream);
+        case 4: return launch_qz<2, 0>(p, nw, g.sub, groups, stream);
+        case 5: return launch_qz<2, 1>(p, nw, g.sub, groups, stream);
+        case 6: return launch_qz<3, 0>(p, nw, g.sub, groups, stream);
+        case 7: return launch_qz<3, 1>(p, nw, g.sub, groups, stream);
+        case 8: return launch_qz<4, 0>(p, nw, g.sub, groups, stream);
+        case 9: return launch_qz<4, 1>(p, nw, g.sub, groups, stream);
     }
     return hipErrorInvalidValue;
 }

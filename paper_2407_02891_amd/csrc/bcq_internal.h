@@ -8,7 +8,8 @@
 namespace bcq {
 
 // Launchers; each returns the hipError_t of its last launch.
-hipError_t launch_pack(const Geom &g, const uint8_t *codes, const uint16_t *alpha,
+// Packs the rows [row0, row0 + rows) of the layer; the sources hold only those rows.
+hipError_t launch_pack(const Geom &g, int row0, int rows, const uint8_t *codes, const uint16_t *alpha,
                        const uint16_t *offset, void *packed, hipStream_t stream);
 hipError_t launch_unpack(const Geom &g, const void *packed, uint8_t *codes, uint16_t *alpha,
                          uint16_t *offset, hipStream_t stream);

@@ -11,14 +11,17 @@
 //   tile bytes:
 //     [t][plane i][lane l]  16 bytes : the 128 sign bits of (row, block kb, plane i)
 //                                      byte j holds the 8 columns 128*kb + 8*c + (0..7),
-//                                      c = (j + r) mod 16, least-significant bit = lowest
-//                                      column.  The rotation by r makes the 16 lanes of a
-//                                      row group address 16 different LDS banks at every
-//                                      step of the table lookups.
-//     [lane l][t][sub][c]   2 bytes  : binary16 alpha_0..alpha_{q-1} (and the offset if
-//                                      present) of (row, block kb, sub-group sub); sub
-//                                      splits the 128 columns when group < 128, and the
-//                                      values are replicated when group > 128.
+//                                      c = chunk_of_byte(j, r, sub), least-significant bit =
+//                                      lowest column.  For sub = 1 this is (j + r) mod 16;
+//                                      in every case the 16 lanes of a row group address 16
+//                                      different LDS banks at every step of the table
+//                                      lookups, and bytes [16/sub * p, 16/sub * (p+1)) of a
+//                                      lane belong to ONE scaling group.
+//     [lane l][t][p][c]     2 bytes  : binary16 alpha_0..alpha_{q-1} (and the offset if
+//                                      present) of (row, block kb) for byte range p of the
+//                                      lane, i.e. of scaling sub-group subgroup_of_range(p,
+//                                      r, sub); sub = 128/group splits the 128 columns when
+//                                      group < 128; the values are replicated when group > 128.
 //
 //   blob = tiles ordered by column slice first, then by row tile, so that a
 //   workgroup, which owns one column slice, streams consecutive memory.
@@ -67,6 +70,29 @@ BCQ_HD inline Geom make_geom(int M, int N, int q, int group, int has_offset)
     g.tile_plane_bytes = 2u * q * 64u * 16u;
     g.tile_bytes = g.tile_plane_bytes + 64u * 2u * g.nsc * 2u;
     return g;
+}
+
+// Which 8-column chunk (0..15) of its 128-column block byte j of lane row r holds, when the
+// block is split into `sub` scaling groups (1, 2 or 4).  The high bits (the sub-group) are
+// XOR-ed with those of r and the low bits rotated by r: a bijection in j for every r, and in
+// r for every j (bank-conflict freedom), that keeps a sub-group in a fixed byte range.
+BCQ_HD inline int chunk_of_byte(int j, int r, int sub)
+{
+    const int lo = 16 / sub - 1, hi = 15 & ~lo;
+    return ((j ^ r) & hi) | ((j + r) & lo);
+}
+
+// Inverse in j: the byte of lane row r that holds chunk c.
+BCQ_HD inline int byte_of_chunk(int c, int r, int sub)
+{
+    const int lo = 16 / sub - 1, hi = 15 & ~lo;
+    return ((c ^ r) & hi) | ((c - r) & lo);
+}
+
+// Scaling sub-group (0..sub-1) of the lane's byte range p (bytes [16/sub*p, 16/sub*(p+1))).
+BCQ_HD inline int subgroup_of_range(int p, int r, int sub)
+{
+    return p ^ ((r * sub) >> 4);
 }
 
 BCQ_HD inline size_t tile_offset(const Geom &g, int slice, int tile)

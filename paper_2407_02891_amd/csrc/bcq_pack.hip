@@ -5,7 +5,14 @@
 
 namespace bcq {
 
-__global__ void pack_planes_kernel(Geom g, const uint8_t *__restrict__ codes,
+// A pack call covers the rows [row0, row0 + rows) of the layer; the call that reaches the last
+// row also writes the padding rows.  `codes`, `alpha`, `offset` hold only the covered rows.
+__device__ __forceinline__ bool row_is_mine(const Geom &g, int row, int row0, int rows)
+{
+    return row >= row0 && (row < row0 + rows || (row >= g.M && row0 + rows == g.M));
+}
+
+__global__ void pack_planes_kernel(Geom g, int row0, int rows, const uint8_t *__restrict__ codes,
                                    uint8_t *__restrict__ blob, size_t total_dwords)
 {
     size_t gid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -19,14 +26,15 @@ __global__ void pack_planes_kernel(Geom g, const uint8_t *__restrict__ codes,
     int r = lane & 15, h = lane >> 4;
     int row = kTileRows * tile + 16 * t + r;
     int kb = 4 * slice + h;
+    if (!row_is_mine(g, row, row0, rows)) return;
     uint32_t word = 0;
     if (row < g.M) {
         for (int n = 0; n < 4; ++n) {
             int j = 4 * d + n;
-            int c = (j + r) & 15;
+            int c = chunk_of_byte(j, r, g.sub);
             int col = kBlockCols * kb + kChunkCols * c;
             if (col < g.N) {
-                const uint8_t *src = codes + (size_t)row * g.N + col;
+                const uint8_t *src = codes + (size_t)(row - row0) * g.N + col;
                 for (int b = 0; b < 8; ++b)
                     word |= (uint32_t)((src[b] >> i) & 1) << (8 * n + b);
             }
@@ -37,7 +45,7 @@ __global__ void pack_planes_kernel(Geom g, const uint8_t *__restrict__ codes,
     *dst = word;
 }
 
-__global__ void pack_scales_kernel(Geom g, const uint16_t *__restrict__ alpha,
+__global__ void pack_scales_kernel(Geom g, int row0, int rows, const uint16_t *__restrict__ alpha,
                                    const uint16_t *__restrict__ offset,
                                    uint8_t *__restrict__ blob, size_t total_entries)
 {
@@ -50,14 +58,15 @@ __global__ void pack_scales_kernel(Geom g, const uint16_t *__restrict__ alpha,
     int lane = e / (2 * g.nsc), rr = e % (2 * g.nsc);
     int t = rr / g.nsc, sc = rr % g.nsc;
     int qz = g.q + g.z;
-    int sub = sc / qz, c = sc % qz;
+    int range = sc / qz, c = sc % qz;
     int r = lane & 15, h = lane >> 4;
     int row = kTileRows * tile + 16 * t + r;
-    int col = kBlockCols * (4 * slice + h) + sub * (kBlockCols / g.sub);
+    if (!row_is_mine(g, row, row0, rows)) return;
+    int col = kBlockCols * (4 * slice + h) + subgroup_of_range(range, r, g.sub) * (kBlockCols / g.sub);
     uint16_t val = 0;
     if (row < g.M && col < g.N) {
-        size_t G = g.N / g.group, grp = col / g.group;
-        val = c < g.q ? alpha[((size_t)row * G + grp) * g.q + c] : offset[(size_t)row * G + grp];
+        size_t G = g.N / g.group, grp = col / g.group, src_row = row - row0;
+        val = c < g.q ? alpha[(src_row * G + grp) * g.q + c] : offset[src_row * G + grp];
     }
     uint16_t *dst = reinterpret_cast<uint16_t *>(blob + tile_offset(g, slice, tile) +
                                                  g.tile_plane_bytes + (size_t)e * 2);
@@ -73,7 +82,7 @@ __global__ void unpack_codes_kernel(Geom g, const uint8_t *__restrict__ blob,
     int slice = col / kTileCols, h = (col % kTileCols) / kBlockCols;
     int c = (col % kBlockCols) / kChunkCols, bit = col % kChunkCols;
     int tile = row / kTileRows, t = (row % kTileRows) / 16, r = row % 16;
-    int j = (c - r) & 15;
+    int j = byte_of_chunk(c, r, g.sub);
     const uint8_t *base = blob + tile_offset(g, slice, tile);
     uint8_t code = 0;
     for (int i = 0; i < g.q; ++i) {
@@ -92,12 +101,13 @@ __global__ void unpack_scales_kernel(Geom g, const uint8_t *__restrict__ blob,
     int row = (int)(gid / G);
     int col = (int)(gid % G) * g.group;           // first column of the group
     int slice = col / kTileCols, h = (col % kTileCols) / kBlockCols;
-    int sub = (col % kBlockCols) / (kBlockCols / g.sub);
     int tile = row / kTileRows, t = (row % kTileRows) / 16, r = row % 16;
+    // subgroup_of_range is its own inverse in its first argument
+    int range = subgroup_of_range((col % kBlockCols) / (kBlockCols / g.sub), r, g.sub);
     int lane = 16 * h + r, qz = g.q + g.z;
     const uint16_t *src = reinterpret_cast<const uint16_t *>(
         blob + tile_offset(g, slice, tile) + g.tile_plane_bytes) +
-        (size_t)lane * 2 * g.nsc + (size_t)t * g.nsc + (size_t)sub * qz;
+        (size_t)lane * 2 * g.nsc + (size_t)t * g.nsc + (size_t)range * qz;
     if (alpha)
         for (int c = 0; c < g.q; ++c) alpha[gid * g.q + c] = src[c];
     if (offset && g.z) offset[gid] = src[g.q];
@@ -115,16 +125,16 @@ static unsigned blocks_for(size_t n, unsigned threads)
     return (unsigned)((n + threads - 1) / threads);
 }
 
-hipError_t launch_pack(const Geom &g, const uint8_t *codes, const uint16_t *alpha,
+hipError_t launch_pack(const Geom &g, int row0, int rows, const uint8_t *codes, const uint16_t *alpha,
                        const uint16_t *offset, void *packed, hipStream_t stream)
 {
     size_t tiles = (size_t)g.nslice * g.ntile;
     size_t nd = tiles * (g.tile_plane_bytes / 4);
     size_t ne = tiles * 64u * 2u * g.nsc;
-    hipLaunchKernelGGL(pack_planes_kernel, dim3(blocks_for(nd, 256)), dim3(256), 0, stream, g, codes,
-                       static_cast<uint8_t *>(packed), nd);
-    hipLaunchKernelGGL(pack_scales_kernel, dim3(blocks_for(ne, 256)), dim3(256), 0, stream, g, alpha,
-                       offset, static_cast<uint8_t *>(packed), ne);
+    hipLaunchKernelGGL(pack_planes_kernel, dim3(blocks_for(nd, 256)), dim3(256), 0, stream, g, row0, rows,
+                       codes, static_cast<uint8_t *>(packed), nd);
+    hipLaunchKernelGGL(pack_scales_kernel, dim3(blocks_for(ne, 256)), dim3(256), 0, stream, g, row0, rows,
+                       alpha, offset, static_cast<uint8_t *>(packed), ne);
     return hipGetLastError();
 }
 

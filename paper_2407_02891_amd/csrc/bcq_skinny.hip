@@ -75,20 +75,41 @@ __device__ __forceinline__ void x_slice_store(uint8_t *xs, int tid, const u32x4 
     }
 }
 
-// Undo the per-row byte rotation of the blob: on return byte s of the 128-bit value is chunk s.
+// Undo the per-row byte permutation of the blob (chunk_of_byte): on return byte s of the
+// 128-bit value is chunk s.
+template <int SUB>
 __device__ __forceinline__ void unrotate(u32x4 &w, int r)
 {
-    const int a = r >> 2, b = r & 3;
-    // rotate left by a dwords: t[d] = w[(d - a) & 3]
-    uint32_t t0 = w.x, t1 = w.y, t2 = w.z, t3 = w.w;
-    if (a & 2) { uint32_t u0 = t2, u1 = t3, u2 = t0, u3 = t1; t0 = u0; t1 = u1; t2 = u2; t3 = u3; }
-    if (a & 1) { uint32_t u0 = t3, u1 = t0, u2 = t1, u3 = t2; t0 = u0; t1 = u1; t2 = u2; t3 = u3; }
-    // rotate left by b bytes across the 128-bit ring
-    const int sh = 32 - 8 * b;  // 32, 24, 16, 8
-    w.x = (uint32_t)((((unsigned long long)t0 << 32) | t3) >> sh);
-    w.y = (uint32_t)((((unsigned long long)t1 << 32) | t0) >> sh);
-    w.z = (uint32_t)((((unsigned long long)t2 << 32) | t1) >> sh);
-    w.w = (uint32_t)((((unsigned long long)t3 << 32) | t2) >> sh);
+    if (SUB == 1) {  // chunk = (byte + r) mod 16: rotate the 128-bit ring left by r bytes
+        const int a = r >> 2, b = r & 3;
+        // rotate left by a dwords: t[d] = w[(d - a) & 3]
+        uint32_t t0 = w.x, t1 = w.y, t2 = w.z, t3 = w.w;
+        if (a & 2) { uint32_t u0 = t2, u1 = t3, u2 = t0, u3 = t1; t0 = u0; t1 = u1; t2 = u2; t3 = u3; }
+        if (a & 1) { uint32_t u0 = t3, u1 = t0, u2 = t1, u3 = t2; t0 = u0; t1 = u1; t2 = u2; t3 = u3; }
+        // rotate left by b bytes across the 128-bit ring
+        const int sh = 32 - 8 * b;  // 32, 24, 16, 8
+        w.x = (uint32_t)((((unsigned long long)t0 << 32) | t3) >> sh);
+        w.y = (uint32_t)((((unsigned long long)t1 << 32) | t0) >> sh);
+        w.z = (uint32_t)((((unsigned long long)t2 << 32) | t1) >> sh);
+        w.w = (uint32_t)((((unsigned long long)t3 << 32) | t2) >> sh);
+    } else if (SUB == 2) {  // rotate each 64-bit half left by r mod 8 bytes, swap the halves if r >= 8
+        unsigned long long lo = ((unsigned long long)w.y << 32) | w.x, hi = ((unsigned long long)w.w << 32) | w.z;
+        lo = __builtin_rotateleft64(lo, 8 * (r & 7));
+        hi = __builtin_rotateleft64(hi, 8 * (r & 7));
+        const unsigned long long a = (r & 8) ? hi : lo, b = (r & 8) ? lo : hi;
+        w.x = (uint32_t)a; w.y = (uint32_t)(a >> 32); w.z = (uint32_t)b; w.w = (uint32_t)(b >> 32);
+    } else {  // rotate each dword left by r mod 4 bytes, dword d goes to d xor (r div 4)
+        const unsigned sh = 8 * (r & 3);
+        uint32_t t0 = __builtin_rotateleft32(w.x, sh), t1 = __builtin_rotateleft32(w.y, sh);
+        uint32_t t2 = __builtin_rotateleft32(w.z, sh), t3 = __builtin_rotateleft32(w.w, sh);
+        // masked exchanges (written without selects so that they stay in registers)
+        const uint32_t m4 = (r & 4) ? 0xffffffffu : 0u, m8 = (r & 8) ? 0xffffffffu : 0u;
+        uint32_t d01 = (t0 ^ t1) & m4, d23 = (t2 ^ t3) & m4;
+        t0 ^= d01; t1 ^= d01; t2 ^= d23; t3 ^= d23;
+        uint32_t d02 = (t0 ^ t2) & m8, d13 = (t1 ^ t3) & m8;
+        t0 ^= d02; t2 ^= d02; t1 ^= d13; t3 ^= d13;
+        w.x = t0; w.y = t1; w.z = t2; w.w = t3;
+    }
 }
 
 // Eight binary16 values (bit ? +|a| : -|a|), after the caller has pre-inverted the word for
@@ -107,15 +128,21 @@ __device__ __forceinline__ f16x8 expand_byte(uint32_t w, uint32_t w_shr4, uint32
     return __builtin_bit_cast(f16x8, a);
 }
 
-template <int Q, int Z>
-__device__ __forceinline__ uint32_t scale_bits(const TileRegs<Q, Z> &t, int th, int c)
+// Scale c of row half t for scaling sub-group g of the block (chunk order).  The lane stores its
+// scales per byte range; the range that holds sub-group g depends on the lane, so every range
+// is read and one is kept (no dynamic register index).
+template <int Q, int Z, int SUB>
+__device__ __forceinline__ uint32_t scale_bits(const TileRegs<Q, Z, SUB> &t, int th, int g, int r, int c)
 {
-    const int e = th * (Q + Z) + c;
-    const uint32_t pair = t.scales[e >> 1];
-    return (e & 1) ? (pair >> 16) : (pair & 0xffffu);
+    const int range = subgroup_of_range(g, r, SUB);  // an involution: range <-> sub-group
+    if (SUB == 1) return scale_bits_of<Q, Z, SUB>(t, th, 0, c);
+    uint32_t v = 0;  // and-or with masks rather than selects: stays in registers
+#pragma unroll
+    for (int k = 0; k < SUB; ++k) v |= scale_bits_of<Q, Z, SUB>(t, th, k, c) & ((range == k) ? 0xffffffffu : 0u);
+    return v;
 }
 
-template <int Q, int Z>
+template <int Q, int Z, int SUB>
 __global__ __launch_bounds__(256) void bcq_skinny_kernel(SkinnyParams p)
 {
     __shared__ __attribute__((aligned(16))) uint8_t xs[2 * kXBufBytes];
@@ -130,8 +157,8 @@ __global__ __launch_bounds__(256) void bcq_skinny_kernel(SkinnyParams p)
     const size_t slice_stride = (size_t)p.ntile * p.tile_bytes;
     const uint8_t *tile_ptr = p.blob + ((size_t)s_begin * p.ntile + (active ? tile : 0)) * p.tile_bytes;
 
-    TileRegs<Q, Z> cur;
-    if (active && s_begin < s_end) load_tile<Q, Z>(cur, tile_ptr, lane);
+    TileRegs<Q, Z, SUB> cur;
+    if (active && s_begin < s_end) load_tile<Q, Z, SUB>(cur, tile_ptr, lane);
     {
         u32x4 xr[4];
         x_slice_load(p, s_begin, tid, xr);
@@ -143,37 +170,51 @@ __global__ __launch_bounds__(256) void bcq_skinny_kernel(SkinnyParams p)
 
     for (int slice = s_begin; slice < s_end; ++slice) {
         const bool more = slice + 1 < s_end;
-        TileRegs<Q, Z> nxt;
+        TileRegs<Q, Z, SUB> nxt;
         u32x4 xr[4];
         tile_ptr += slice_stride;
         if (more) {
-            if (active) load_tile<Q, Z>(nxt, tile_ptr, lane);
+            if (active) load_tile<Q, Z, SUB>(nxt, tile_ptr, lane);
             x_slice_load(p, slice + 1, tid, xr);
         }
         if (active) {
             // per (row half, plane): un-rotate, fold the sign of alpha into the bits, |alpha| pair
-            uint32_t abs_pair[2][Q];
-            uint32_t z_pair[2];
+            uint32_t abs_pair[2][Q][SUB];
+            uint32_t z_pair[2][SUB];
 #pragma unroll
             for (int t = 0; t < 2; ++t) {
 #pragma unroll
                 for (int i = 0; i < Q; ++i) {
-                    const uint32_t ab = scale_bits<Q, Z>(cur, t, i);
-                    const uint32_t flip = (ab & 0x8000u) ? 0u : 0xffffffffu;  // bit 1 <-> +1
-                    u32x4 &w = cur.planes[t][i];
-                    unrotate(w, r);
-                    w.x ^= flip; w.y ^= flip; w.z ^= flip; w.w ^= flip;
-                    const uint32_t mag = ab & 0x7fffu;
-                    abs_pair[t][i] = mag | (mag << 16);
+                    u32x4 w = cur.planes[t][i];
+                    unrotate<SUB>(w, r);
+                    uint32_t flip[SUB];
+#pragma unroll
+                    for (int g = 0; g < SUB; ++g) {
+                        const uint32_t ab = scale_bits<Q, Z, SUB>(cur, t, g, r, i);
+                        flip[g] = (ab & 0x8000u) ? 0u : 0xffffffffu;  // bit 1 <-> +1
+                        const uint32_t mag = ab & 0x7fffu;
+                        abs_pair[t][i][g] = mag | (mag << 16);
+                    }
+                    // dword d of the un-permuted value belongs to sub-group d * SUB / 4
+                    w.x ^= flip[0];
+                    w.y ^= flip[SUB == 4 ? 1 : 0];
+                    w.z ^= flip[SUB == 4 ? 2 : SUB - 1];
+                    w.w ^= flip[SUB - 1];
+                    cur.planes[t][i] = w;
                 }
                 if (Z) {
-                    const uint32_t zb = scale_bits<Q, Z>(cur, t, Q);
-                    z_pair[t] = zb | (zb << 16);
+#pragma unroll
+                    for (int g = 0; g < SUB; ++g) {
+                        const uint32_t zb = scale_bits<Q, Z, SUB>(cur, t, g, r, Q);
+                        z_pair[t][g] = zb | (zb << 16);
+                    }
                 }
             }
             const uint8_t *xb = xs + (slice - s_begin & 1) * kXBufBytes + r * kXPitchBytes + h * 256;
 #pragma unroll
             for (int dq = 0; dq < 4; ++dq) {
+                constexpr int per = 4 / SUB;  // dwords (of 4 chunks) per scaling sub-group
+                const int g = dq / per;
                 uint32_t w[2][Q], w4[2][Q];
 #pragma unroll
                 for (int t = 0; t < 2; ++t)
@@ -190,14 +231,14 @@ __global__ __launch_bounds__(256) void bcq_skinny_kernel(SkinnyParams p)
 #pragma unroll
                         for (int i = 0; i < Q; ++i) {
                             f16x8 a;
-                            if (n == 0) a = expand_byte<0>(w[t][i], w4[t][i], abs_pair[t][i]);
-                            if (n == 1) a = expand_byte<1>(w[t][i], w4[t][i], abs_pair[t][i]);
-                            if (n == 2) a = expand_byte<2>(w[t][i], w4[t][i], abs_pair[t][i]);
-                            if (n == 3) a = expand_byte<3>(w[t][i], w4[t][i], abs_pair[t][i]);
+                            if (n == 0) a = expand_byte<0>(w[t][i], w4[t][i], abs_pair[t][i][g]);
+                            if (n == 1) a = expand_byte<1>(w[t][i], w4[t][i], abs_pair[t][i][g]);
+                            if (n == 2) a = expand_byte<2>(w[t][i], w4[t][i], abs_pair[t][i][g]);
+                            if (n == 3) a = expand_byte<3>(w[t][i], w4[t][i], abs_pair[t][i][g]);
                             acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, bx, acc[t], 0, 0, 0);
                         }
                         if (Z) {
-                            const u32x4 zz = {z_pair[t], z_pair[t], z_pair[t], z_pair[t]};
+                            const u32x4 zz = {z_pair[t][g], z_pair[t][g], z_pair[t][g], z_pair[t][g]};
                             acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, zz), bx, acc[t],
                                                                             0, 0, 0);
                         }
@@ -263,11 +304,19 @@ int auto_skinny_parts(const Geom &g)
     return parts;
 }
 
-template <int Q, int Z>
-static hipError_t launch_skinny_qz(const SkinnyParams &p, hipStream_t stream)
+template <int Q, int Z, int SUB>
+static hipError_t launch_skinny_one(const SkinnyParams &p, hipStream_t stream)
 {
-    hipLaunchKernelGGL((bcq_skinny_kernel<Q, Z>), dim3((unsigned)(p.ntg * p.parts)), dim3(256), 0, stream, p);
+    hipLaunchKernelGGL((bcq_skinny_kernel<Q, Z, SUB>), dim3((unsigned)(p.ntg * p.parts)), dim3(256), 0, stream, p);
     return hipGetLastError();
+}
+
+template <int Q, int Z>
+static hipError_t launch_skinny_qz(const SkinnyParams &p, int sub, hipStream_t stream)
+{
+    if (sub == 2) return launch_skinny_one<Q, Z, 2>(p, stream);
+    if (sub == 4) return launch_skinny_one<Q, Z, 4>(p, stream);
+    return launch_skinny_one<Q, Z, 1>(p, stream);
 }
 
 hipError_t launch_skinny(const Geom &g, const void *packed, const uint16_t *X, int ldx, uint16_t *Y, int ldy,
@@ -284,14 +333,14 @@ hipError_t launch_skinny(const Geom &g, const void *packed, const uint16_t *X, i
     if (!workspace) p.parts = 1;  // only reachable for a single column slice
     p.tile_bytes = g.tile_bytes;
     switch (g.q * 2 + g.z) {
-        case 2: return launch_skinny_qz<1, 0>(p, stream);
-        case 3: return launch_skinny_qz<1, 1>(p, stream);
-        case 4: return launch_skinny_qz<2, 0>(p, stream);
-        case 5: return launch_skinny_qz<2, 1>(p, stream);
-        case 6: return launch_skinny_qz<3, 0>(p, stream);
-        case 7: return launch_skinny_qz<3, 1>(p, stream);
-        case 8: return launch_skinny_qz<4, 0>(p, stream);
-        case 9: return launch_skinny_qz<4, 1>(p, stream);
+        case 2: return launch_skinny_qz<1, 0>(p, g.sub, stream);
+        case 3: return launch_skinny_qz<1, 1>(p, g.sub, stream);
+        case 4: return launch_skinny_qz<2, 0>(p, g.sub, stream);
+        case 5: return launch_skinny_qz<2, 1>(p, g.sub, stream);
+        case 6: return launch_skinny_qz<3, 0>(p, g.sub, stream);
+        case 7: return launch_skinny_qz<3, 1>(p, g.sub, stream);
+        case 8: return launch_skinny_qz<4, 0>(p, g.sub, stream);
+        case 9: return launch_skinny_qz<4, 1>(p, g.sub, stream);
     }
     return hipErrorInvalidValue;
 }

@@ -57,8 +57,8 @@ def test_packed_bytes_pads_ragged_shapes():
     ((16, 256, 3, 96, 0), B.BCQ_ERR_INVALID_ARG),       # group does not divide N
     ((16, 256, 3, 128, 2), B.BCQ_ERR_INVALID_ARG),
     ((16, 256, 5, 128, 0), B.BCQ_ERR_UNSUPPORTED),      # q > 4
-    ((16, 384, 3, 96, 0), B.BCQ_ERR_UNSUPPORTED),       # group neither k*128 nor N
-    ((16, 384, 3, 64, 0), B.BCQ_ERR_UNSUPPORTED),
+    ((16, 384, 3, 96, 0), B.BCQ_ERR_UNSUPPORTED),       # group not 32, 64, k*128 or N
+    ((16, 640, 3, 160, 0), B.BCQ_ERR_UNSUPPORTED),
 ])
 def test_bad_descriptors_are_refused_before_launch(fields, status):
     d = bcq.Desc(*fields, 0)
@@ -68,6 +68,26 @@ def test_bad_descriptors_are_refused_before_launch(fields, status):
     # non-NULL dummy pointers: validation must fail before they are ever used
     rc = L.bcq_pack(ctypes.byref(d), 256, 256, None, 256, None)
     assert rc == status
+
+
+def test_small_groups_are_sized_with_one_scale_set_per_group():
+    for group, sub in ((32, 4), (64, 2), (128, 1)):
+        d = bcq.Desc(32, 512, 3, group, 1, 0)
+        assert bcq.packed_bytes(d) == 2 * 3 * 1024 + 64 * 2 * sub * 4 * 2
+
+
+def test_pack_rows_argument_checks():
+    L = bcq.lib()
+    d = bcq.Desc(64, 1024, 3, 128, 0, 0)
+    ok = (256, 256, None, 256, None)  # codes, alpha, offset, packed, stream
+    assert L.bcq_pack_rows(ctypes.byref(d), -1, 8, *ok) == B.BCQ_ERR_INVALID_ARG
+    assert L.bcq_pack_rows(ctypes.byref(d), 0, 0, *ok) == B.BCQ_ERR_INVALID_ARG
+    assert L.bcq_pack_rows(ctypes.byref(d), 60, 5, *ok) == B.BCQ_ERR_INVALID_ARG      # past the last row
+    assert L.bcq_pack_rows(ctypes.byref(d), 0, 8, None, 256, None, 256, None) == B.BCQ_ERR_INVALID_ARG
+    assert L.bcq_pack_rows(ctypes.byref(d), 0, 8, 256, 256, 256, 256, None) == B.BCQ_ERR_INVALID_ARG  # offset w/o flag
+    assert L.bcq_pack_rows(ctypes.byref(d), 0, 8, 256, 256, None, 255, None) == B.BCQ_ERR_INVALID_ARG  # misaligned
+    assert d.layout_version == 0
+    assert L.bcq_pack_rows(None, 0, 8, *ok) == B.BCQ_ERR_INVALID_ARG
 
 
 def test_gemv_argument_checks():

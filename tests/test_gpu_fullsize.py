@@ -55,3 +55,32 @@ def test_llama70b_shapes(M, N, q):
 def test_skinny_fullsize(M, N, q, offset, batch):
     """configs[2] (q=2 with offset, batch 8) and configs[3] (batch 4 and 16, outlier channels)"""
     _check(M, N, q, offset, batch=batch, outlier_frac=0.01 if M == 9216 else 0.0)
+
+
+def test_llama70b_fused_qkv_equals_three_gemvs():
+    """configs[4]: the q, k and v projections (8192, 1024, 1024 rows of 8192 columns) read the
+    same activations.  Packed row-wise into one blob (bcq_pack_rows) they run as ONE GEMV whose
+    output is, bit for bit, the concatenation of the three separate GEMVs, and matches the oracle."""
+    import torch
+    import paper_2407_02891_amd as bcq
+    N, q = 8192, 3
+    parts = [bcq_synth.make_layer(M, N, q, group=128, offset=False, seed=s) for s, M in enumerate((8192, 1024, 1024))]
+    xd = U.x_dev(parts[0])
+    fused = bcq.PackedLayer(sum(L.M for L in parts), N, q, 128, False)
+    row0, separate = 0, []
+    for L in parts:
+        codes = U.to_dev(L.codes())
+        alpha = U.to_dev(L.alpha.view(np.uint16).astype(np.int16)).view(torch.float16)
+        fused.pack_rows_from(row0, codes, alpha, None)
+        row0 += L.M
+        separate.append(U.gpu_gemv(U.upload_and_pack(L), xd))
+    y = U.gpu_gemv(fused, xd)
+    assert np.array_equal(y.view(np.uint16), np.concatenate(separate).view(np.uint16))
+    row0 = 0
+    for L in parts:
+        rows = _sample_rows(L.M, n=96)
+        planes, alpha = np.ascontiguousarray(L.planes[:, rows]), np.ascontiguousarray(L.alpha[rows])
+        from oracle import ref
+        y_ref = ref.gemm(planes, alpha, None, parts[0].x)
+        U.gate(y[None, row0 + rows], y_ref, f"fused qkv part at row {row0}")
+        row0 += L.M

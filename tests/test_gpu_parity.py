@@ -173,3 +173,57 @@ def test_skinny_negative_alpha_and_ragged():
     # the batch-1 kernel on the same layer
     y1 = U.gpu_gemv(pl, U.x_dev(L))
     U.gate(y1[None, :], ref.gemm(L.planes, L.alpha, L.offset, L.x[:1]))
+
+
+@pytest.mark.parametrize("group", [32, 64])
+@pytest.mark.parametrize("q,offset", [(3, False), (2, True), (4, True), (1, False)])
+def test_small_groups(group, q, offset):
+    """Groups of 32 and 64 columns: 4 or 2 scale sets per 128-column block, batch 1 and skinny."""
+    _run_case(203, 1600, q, group, offset, seed=group + q)          # ragged rows and columns
+    _run_case(96, 2048, q, group, offset, batch=5, seed=group + q + 1)
+
+
+@pytest.mark.parametrize("group", [32, 64])
+def test_small_groups_exact_and_roundtrip(group):
+    """Bit-exact result on exactly representable inputs and pack -> unpack identity for the
+    permuted byte order used when a block holds several scaling groups."""
+    L = bcq_synth.make_exact_layer(150, 1536, 3, group=group, offset=True, batch=3, seed=group)
+    pl = U.upload_and_pack(L, max_batch=3)
+    y_ref = ref.gemm(L.planes, L.alpha, L.offset, L.x)
+    expect = y_ref.astype(np.float16).astype(np.float64)
+    xd = U.x_dev(L)
+    assert np.array_equal(U.gpu_gemv(pl, xd[0]).astype(np.float64), expect[0])
+    assert np.array_equal(U.gpu_gemm(pl, xd).astype(np.float64), expect)
+    G = L.N // group
+    codes = torch.empty((L.M, L.N), dtype=torch.uint8, device="cuda")
+    alpha = torch.empty((L.M, G, L.q), dtype=torch.float16, device="cuda")
+    off = torch.empty((L.M, G), dtype=torch.float16, device="cuda")
+    bcq.unpack(pl.desc, pl.packed, codes, alpha, off)
+    torch.cuda.synchronize()
+    assert np.array_equal(codes.cpu().numpy(), L.codes())
+    assert np.array_equal(alpha.cpu().numpy().view(np.uint16), L.alpha.view(np.uint16))
+    assert np.array_equal(off.cpu().numpy().view(np.uint16), L.offset.view(np.uint16))
+
+
+def _rows_of(L, lo, hi):
+    codes = U.to_dev(L.codes()[lo:hi])
+    alpha = U.to_dev(L.alpha[lo:hi].view(np.uint16).astype(np.int16)).view(torch.float16)
+    off = None if L.offset is None else U.to_dev(L.offset[lo:hi].view(np.uint16).astype(np.int16)).view(torch.float16)
+    return codes, alpha, off
+
+
+@pytest.mark.parametrize("group,offset", [(128, True), (64, False)])
+def test_pack_rows_builds_the_same_blob_as_one_pack(group, offset):
+    """Layers sharing their input, packed range by range into one blob (ranges that do not
+    fall on tile boundaries, packed out of order), give byte for byte the blob of a single
+    bcq_pack of the stacked layer, hence the same product."""
+    L = bcq_synth.make_layer(203, 1152, 3, group=group, offset=offset, seed=41)
+    whole = U.upload_and_pack(L)
+    fused = bcq.PackedLayer(L.M, L.N, L.q, L.group, L.offset is not None)
+    fused.packed.fill_(0xA5)
+    for lo, hi in ((150, 203), (0, 37), (37, 150)):
+        fused.pack_rows_from(lo, *_rows_of(L, lo, hi))
+    torch.cuda.synchronize()
+    assert torch.equal(fused.packed, whole.packed)
+    y = U.gpu_gemv(fused, U.x_dev(L))
+    U.gate(y[None, :], ref.gemm(L.planes, L.alpha, L.offset, L.x), "fused rows")
