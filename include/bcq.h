@@ -105,6 +105,29 @@ bcq_status bcq_pack(bcq_desc *desc, const uint8_t *codes, const uint16_t *alpha,
                     const uint16_t *offset, void *packed, void *stream);
 
 /*
+ * Result of the paper's two-step quantiser -> operands of bcq_pack (Sec. II-B Eq. 6, Sec. II-D
+ * Eq. 8-11).  The quantiser leaves n_bits-bit linear integers W_int, one scale S and one bias
+ * qbias per scaling group (W_hat = S * W_int + qbias), and a tying of the n_bits linear
+ * bit-planes into q classes that share one sign each (Eq. 10 ties planes 2 and 3 of three).
+ *   class_of_plane HOST [n_bits]: class (0..q-1) of linear plane i+1, i.e. of bit i of W_int,
+ *                  whose weight in Eq. 9 is 2^(i-1); every class must be non-empty
+ *   w_int   DEVICE [M][N] uint8, values 0 .. 2^n_bits - 1 (higher bits ignored)
+ *   S, qbias DEVICE [M][N/group] binary32
+ *   codes   DEVICE [M][N] uint8 out: bit o = sign of fused plane o (1 means +1)
+ *   alpha   DEVICE [M][N/group][q] binary16 out: S * alpha_hat_o, alpha_hat_o = sum of 2^(i-1)
+ *           over the bits i tied into plane o; planes ordered by descending alpha_hat
+ *   offset  DEVICE [M][N/group] binary16 out: (2^n_bits - 1)/2 * S + qbias
+ * Every W_int is first replaced by the nearest integer the tying can represent (Eq. 6; a tie
+ * goes to the smaller one), so integers already in that set pass unchanged.  alpha and offset
+ * are evaluated in binary64 and rounded once to binary16 (nearest even).  Use has_offset = 1
+ * in the descriptor given to bcq_pack.  Offline step.
+ */
+bcq_status bcq_from_linear(int32_t M, int32_t N, int32_t group, int32_t n_bits, int32_t q,
+                           const int32_t *class_of_plane, const uint8_t *w_int, const float *S,
+                           const float *qbias, uint8_t *codes, uint16_t *alpha, uint16_t *offset,
+                           void *stream);
+
+/*
  * bcq_pack for a range of rows: writes the rows [row_begin, row_begin + rows) of the layer
  * `desc` describes from sources that hold ONLY those rows (codes [rows][N], alpha
  * [rows][N/group][q], offset [rows][N/group]).  Layers that are applied to the same

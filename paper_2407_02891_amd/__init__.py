@@ -3,6 +3,6 @@
 Thin Python binding over the C ABI in include/bcq.h; see `binding`.
 """
 from .binding import (  # noqa: F401
-    BcqError, Desc, PackedLayer, gemm_skinny, gemv, lib, pack, pack_rows, packed_bytes,
+    BcqError, Desc, PackedLayer, from_linear, gemm_skinny, gemv, lib, pack, pack_rows, packed_bytes,
     read_probe, set_option, status_string, unpack, workspace_bytes, workspace_init,
 )

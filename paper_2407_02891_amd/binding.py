@@ -13,7 +13,7 @@ BCQ_LAYOUT_VERSION = 1
 BCQ_MAX_BATCH = 16
 
 EXPORTS = ["bcq_packed_bytes", "bcq_workspace_bytes", "bcq_workspace_init", "bcq_pack",
-           "bcq_pack_rows", "bcq_unpack", "bcq_gemv", "bcq_gemm_skinny", "bcq_read_probe_sink_bytes",
+           "bcq_pack_rows", "bcq_from_linear", "bcq_unpack", "bcq_gemv", "bcq_gemm_skinny", "bcq_read_probe_sink_bytes",
            "bcq_read_probe", "bcq_set_option", "bcq_status_string"]
 
 
@@ -48,6 +48,8 @@ def lib():
         L.bcq_workspace_init.restype, L.bcq_workspace_init.argtypes = i32, [vp, sz, vp]
         L.bcq_pack.restype, L.bcq_pack.argtypes = i32, [dp, vp, vp, vp, vp, vp]
         L.bcq_pack_rows.restype, L.bcq_pack_rows.argtypes = i32, [dp, i32, i32, vp, vp, vp, vp, vp]
+        L.bcq_from_linear.restype = i32
+        L.bcq_from_linear.argtypes = [i32, i32, i32, i32, i32, ctypes.POINTER(ctypes.c_int32), vp, vp, vp, vp, vp, vp, vp]
         L.bcq_unpack.restype, L.bcq_unpack.argtypes = i32, [dp, vp, vp, vp, vp, vp]
         L.bcq_gemv.restype, L.bcq_gemv.argtypes = i32, [dp, vp, vp, vp, vp, vp]
         L.bcq_gemm_skinny.restype = i32
@@ -109,6 +111,14 @@ def pack(desc, codes, alpha, offset, packed, stream=None):
 def pack_rows(desc, row_begin, rows, codes, alpha, offset, packed, stream=None):
     _check(lib().bcq_pack_rows(ctypes.byref(desc), int(row_begin), int(rows), _ptr(codes), _ptr(alpha),
                                _ptr(offset), _ptr(packed), _stream(stream)), "bcq_pack_rows")
+
+
+def from_linear(M, N, group, n_bits, q, class_of_plane, w_int, S, qbias, codes, alpha, offset, stream=None):
+    """class_of_plane: sequence of n_bits ints (host); the rest are device tensors."""
+    labels = (ctypes.c_int32 * len(class_of_plane))(*[int(c) for c in class_of_plane])
+    _check(lib().bcq_from_linear(int(M), int(N), int(group), int(n_bits), int(q), labels, _ptr(w_int), _ptr(S),
+                                 _ptr(qbias), _ptr(codes), _ptr(alpha), _ptr(offset), _stream(stream)),
+           "bcq_from_linear")
 
 
 def unpack(desc, packed, codes, alpha, offset, stream=None):

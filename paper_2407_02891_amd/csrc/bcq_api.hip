@@ -87,6 +87,28 @@ bcq_status bcq_pack(bcq_desc *desc, const uint8_t *codes, const uint16_t *alpha,
     return bcq_pack_rows(desc, 0, desc->M, codes, alpha, offset, packed, stream);
 }
 
+bcq_status bcq_from_linear(int32_t M, int32_t N, int32_t group, int32_t n_bits, int32_t q,
+                           const int32_t *class_of_plane, const uint8_t *w_int, const float *S,
+                           const float *qbias, uint8_t *codes, uint16_t *alpha, uint16_t *offset, void *stream)
+{
+    if (M <= 0 || N <= 0 || group <= 0 || N % group != 0) return BCQ_ERR_INVALID_ARG;
+    if (n_bits < 1 || n_bits > 8 || q < 1 || q > n_bits || !class_of_plane) return BCQ_ERR_INVALID_ARG;
+    if (q > kMaxQ) return BCQ_ERR_UNSUPPORTED;
+    if (!w_int || !S || !qbias || !codes || !alpha || !offset) return BCQ_ERR_INVALID_ARG;
+    if (!aligned(S, 4) || !aligned(qbias, 4) || !aligned(alpha, 2) || !aligned(offset, 2)) return BCQ_ERR_INVALID_ARG;
+    bool seen[kMaxQ] = {false, false, false, false};
+    for (int i = 0; i < n_bits; ++i) {
+        if (class_of_plane[i] < 0 || class_of_plane[i] >= q) return BCQ_ERR_INVALID_ARG;
+        seen[class_of_plane[i]] = true;
+    }
+    for (int c = 0; c < q; ++c)
+        if (!seen[c]) return BCQ_ERR_INVALID_ARG;  // an empty class
+    return launch_from_linear(M, N, group, n_bits, q, class_of_plane, w_int, S, qbias, codes, alpha, offset,
+                              static_cast<hipStream_t>(stream)) == hipSuccess
+               ? BCQ_OK
+               : BCQ_ERR_HIP;
+}
+
 bcq_status bcq_unpack(const bcq_desc *desc, const void *packed, uint8_t *codes, uint16_t *alpha,
                       uint16_t *offset, void *stream)
 {

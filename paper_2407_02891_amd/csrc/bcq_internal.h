@@ -14,6 +14,13 @@ hipError_t launch_pack(const Geom &g, int row0, int rows, const uint8_t *codes, 
 hipError_t launch_unpack(const Geom &g, const void *packed, uint8_t *codes, uint16_t *alpha,
                          uint16_t *offset, hipStream_t stream);
 hipError_t launch_fill_zero(void *ptr, size_t bytes, hipStream_t stream);
+// Linear n-bit integers + per-group scale/bias + plane tying -> codes, fused alpha, fused offset
+// (Eq. 6, 9-11).  hipErrorInvalidValue if the tying is malformed.
+hipError_t launch_from_linear(int M, int N, int group, int n_bits, int q, const int32_t *class_of_plane,
+                              const uint8_t *w_int, const float *S, const float *qbias, uint8_t *codes,
+                              uint16_t *alpha, uint16_t *offset, hipStream_t stream);
+struct ConvertPlan;
+bool make_convert_plan(int n_bits, int q, const int32_t *class_of_plane, ConvertPlan *plan);
 // Launch shape of the GEMV (bcq_set_option); zeros mean "choose automatically".
 struct GemvTuning {
     int workgroups = 0; // grid size

@@ -131,6 +131,27 @@ def test_pack_pointer_checks():
     assert d0.layout_version == 0
 
 
+def test_from_linear_argument_checks():
+    L = bcq.lib()
+    ok = 0x1000
+    labels = lambda *v: (ctypes.c_int32 * len(v))(*v)
+    f = lambda M, N, g, n, q, lab, *ptrs: L.bcq_from_linear(M, N, g, n, q, lab, *(ptrs or (ok,) * 6), None)
+    good = labels(0, 1, 1)
+    assert f(0, 256, 128, 3, 2, good) == B.BCQ_ERR_INVALID_ARG
+    assert f(16, 256, 96, 3, 2, good) == B.BCQ_ERR_INVALID_ARG          # group does not divide N
+    assert f(16, 256, 128, 9, 2, good) == B.BCQ_ERR_INVALID_ARG         # more than 8 linear bits
+    assert f(16, 256, 128, 3, 4, labels(0, 1, 2)) == B.BCQ_ERR_INVALID_ARG   # more classes than planes
+    assert f(16, 256, 128, 3, 2, labels(0, 0, 0)) == B.BCQ_ERR_INVALID_ARG   # class 1 empty
+    assert f(16, 256, 128, 3, 2, labels(0, 2, 1)) == B.BCQ_ERR_INVALID_ARG   # label out of range
+    assert f(16, 256, 128, 3, 2, None) == B.BCQ_ERR_INVALID_ARG
+    assert f(16, 256, 128, 6, 5, labels(0, 1, 2, 3, 4, 4)) == B.BCQ_ERR_UNSUPPORTED  # q > 4
+    for k in range(6):
+        ptrs = [ok] * 6
+        ptrs[k] = None
+        assert f(16, 256, 128, 3, 2, good, *ptrs) == B.BCQ_ERR_INVALID_ARG
+    assert f(16, 256, 128, 3, 2, good, ok, ok + 2, ok, ok, ok, ok) == B.BCQ_ERR_INVALID_ARG  # S misaligned
+
+
 def test_misc_argument_checks():
     L = bcq.lib()
     assert L.bcq_workspace_init(None, 64, None) == B.BCQ_ERR_INVALID_ARG
