@@ -57,6 +57,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=12)
     ap.add_argument("--workload", choices=sorted(WORKLOADS), default="opt30b")
     ap.add_argument("--q", type=int, choices=(2, 3), default=3, help="number of sign planes")
+    ap.add_argument("--batch", type=int, default=1,
+                    help="activation vectors per call: 1 = bcq_gemv (the headline), 2..16 = bcq_gemm_skinny")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -83,6 +85,10 @@ def main():
     def to_dev(a):
         return torch.from_numpy(np.ascontiguousarray(a)).to(dev)
 
+    if not 1 <= args.batch <= 16:
+        print("bench.py: --batch must be 1..16", file=sys.stderr)
+        sys.exit(2)
+    B = args.batch
     LAUNCHES, DOMINANT, WORKLOAD_TEXT = WORKLOADS[args.workload]
     LAYERS = [(name, sum(rows for _, rows in parts), N) for name, parts, N in LAUNCHES]
     Q = args.q
@@ -92,10 +98,10 @@ def main():
     total_bytes = 0
     for name, parts, N in LAUNCHES:
         M = sum(rows for _, rows in parts)
-        pl = bcq.PackedLayer(M, N, Q, GROUP, False)
+        pl = bcq.PackedLayer(M, N, Q, GROUP, False, max_batch=B)
         subs, row0, nbytes = [], 0, 0
         for k, (pname, rows) in enumerate(parts):  # each projection from its own tensors
-            L = bcq_synth.make_layer(rows, N, Q, group=GROUP, offset=False, batch=1, seed=k)
+            L = bcq_synth.make_layer(rows, N, Q, group=GROUP, offset=False, batch=B, seed=k)
             codes = to_dev(L.codes())
             alpha = to_dev(L.alpha.view(np.uint16).astype(np.int16)).view(torch.float16)
             pl.pack_rows_from(row0, codes, alpha, None)
@@ -104,8 +110,8 @@ def main():
             subs.append((row0, L))
             row0 += rows
             nbytes += L.weight_bytes()
-        x = to_dev(subs[0][1].x.view(np.uint16).astype(np.int16)).view(torch.float16)[0]
-        y = torch.empty(M, dtype=torch.float16, device=dev)
+        x = to_dev(subs[0][1].x.view(np.uint16).astype(np.int16)).view(torch.float16)  # [B][N]
+        y = torch.empty((B, M), dtype=torch.float16, device=dev)
         layers[name] = dict(subs=subs, pl=pl, x=x, y=y, bytes=nbytes, copies=[pl.packed])
         total_bytes += nbytes
     n_copies = max(2, math.ceil(1.25 * 2 ** 30 / total_bytes))
@@ -117,8 +123,12 @@ def main():
     def launch(name, i):
         ent = layers[name]
         pl = ent["pl"]
-        bcq.gemv(pl.desc, ent["copies"][i % n_copies], ent["x"], ent["y"],
-                 pl.workspace if pl.workspace_bytes else None)
+        ws = pl.workspace if pl.workspace_bytes else None
+        if B == 1:
+            bcq.gemv(pl.desc, ent["copies"][i % n_copies], ent["x"], ent["y"], ws)
+        else:
+            bcq.gemm_skinny(pl.desc, ent["copies"][i % n_copies], ent["x"], ent["x"].stride(0), ent["y"],
+                            ent["y"].stride(0), B, ws)
 
     def step(i):
         for name, _, _ in LAYERS:
@@ -177,13 +187,26 @@ def main():
                                pct_of_hbm_peak=round(layers[name]["bytes"] / us / 1e3 / HBM_PEAK_GBS * 100, 2))
     dom = per_layer[DOMINANT]
     achieved = dom["weight_bytes"] / (dom["us_per_gemv"] * 1e-6) / 1e9
-    roofline = dict(bound="hbm", kernel="bcq_gemv_kernel (q=%d, no offset, group 128) on %dx%d" % (Q, dom["M"], dom["N"]),
-                    achieved=round(achieved, 1),
-                    peak=HBM_PEAK_GBS, unit="GB/s", frac=round(achieved / HBM_PEAK_GBS, 4),
-                    bytes_per_launch=dom["weight_bytes"], us_per_launch=dom["us_per_gemv"], traffic=None)
+    if B > 1:
+        # The single-pass skinny kernel is bound by the vector ALU work of expanding sign bits into
+        # binary16 operands for the matrix cores: 9 lane-operations per 8 signs.  Peak = 256 CUs x 4
+        # SIMDs x 16 lanes x 2.4 GHz = 39.3 T lane-op/s.
+        lane_ops = 9.0 / 8.0 * Q * dom["M"] * dom["N"]
+        alu = lane_ops / (dom["us_per_gemv"] * 1e-6) / 1e12
+        roofline = dict(bound="alu", kernel="bcq_skinny_kernel (q=%d, no offset, group 128, batch %d) on %dx%d"
+                                            % (Q, B, dom["M"], dom["N"]),
+                        achieved=round(alu, 2), peak=39.3, unit="T lane-op/s", frac=round(alu / 39.3, 4),
+                        lane_ops_per_launch=lane_ops, us_per_launch=dom["us_per_gemv"], traffic=None,
+                        weight_GBps=dom["weight_GBps"])
+    else:
+        roofline = dict(bound="hbm",
+                        kernel="bcq_gemv_kernel (q=%d, no offset, group 128) on %dx%d" % (Q, dom["M"], dom["N"]),
+                        achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s",
+                        frac=round(achieved / HBM_PEAK_GBS, 4), bytes_per_launch=dom["weight_bytes"],
+                        us_per_launch=dom["us_per_gemv"], traffic=None)
     # HBM bytes per launch measured separately with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE); see profiles/
     traffic_file = os.path.join(ROOT, "profiles", "bcq_gemv_opt30b_q3_hbm_traffic.md")
-    if os.path.exists(traffic_file) and args.workload == "opt30b" and Q == 3:
+    if os.path.exists(traffic_file) and args.workload == "opt30b" and Q == 3 and B == 1:
         for line in open(traffic_file):
             if line.startswith("hbm_bytes_per_launch_fc2"):
                 roofline["traffic"] = float(line.split("=")[1])
@@ -199,8 +222,8 @@ def main():
             x0 = layers[name]["subs"][0][1].x  # the activations every part of this launch was given
             y_all = layers[name]["y"].cpu().numpy().astype(np.float64)
             for row0, L in layers[name]["subs"]:
-                y_ref = ref.gemm(L.planes, L.alpha, None, x0)[0]
-                y_gpu = y_all[row0:row0 + L.M]
+                y_ref = ref.gemm(L.planes, L.alpha, None, x0)
+                y_gpu = y_all[:, row0:row0 + L.M]
                 rms = math.sqrt(float(np.mean(y_ref ** 2)))
                 err = np.abs(y_gpu - y_ref) / np.maximum(np.abs(y_ref), rms / 64.0)
                 worst = max(worst, float(err.max()))
@@ -211,12 +234,12 @@ def main():
         parity = dict(max_gated_rel_err=worst, tolerance=2e-3)
 
     out = {
-        "metric": "effective weight GB/s (and us per GEMV), %d-bit batch-1 binary-coding GEMV" % Q,
+        "metric": "effective weight GB/s (and us per GEMV), %d-bit batch-%d binary-coding GEMV" % (Q, B),
         "value": round(value_gbs, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16 activations, 1-bit planes x%d, f32 accumulate" % Q, "data": "synthetic",
-        "config": {"workload": "%s, q=%d, group=128, batch=1, cold weights (%d rotating copies)"
-                               % (WORKLOAD_TEXT, Q, n_copies), "launches_per_step": len(LAYERS),
+        "config": {"workload": "%s, q=%d, group=128, batch=%d, cold weights (%d rotating copies)"
+                               % (WORKLOAD_TEXT, Q, B, n_copies), "launches_per_step": len(LAYERS),
                    "weight_bytes_per_step": total_bytes, "launch": "graph" if not args.no_graph else "eager"},
         "pct_of_hbm_peak": round(value_gbs / HBM_PEAK_GBS * 100, 2),
         "layers": per_layer, "roofline": roofline, "cpu_baseline": cpu, "parity": parity,

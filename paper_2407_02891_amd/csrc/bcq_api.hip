@@ -138,7 +138,7 @@ bcq_status bcq_gemm_skinny(const bcq_desc *desc, const void *packed, const uint1
     hipStream_t s = static_cast<hipStream_t>(stream);
     // batch 1: the table-lookup GEMV (HBM-bound); batch >= 2: the matrix-core kernel, weights read once
     hipError_t e = batch == 1 ? launch_gemv(g, packed, X, Y, workspace, g_tuning, s)
-                              : launch_skinny(g, packed, X, ldx, Y, ldy, batch, workspace, g_tuning.skinny_parts, s);
+                              : launch_skinny(g, packed, X, ldx, Y, ldy, batch, workspace, g_tuning, s);
     return e == hipSuccess ? BCQ_OK : BCQ_ERR_HIP;
 }
 
@@ -172,6 +172,14 @@ bcq_status bcq_set_option(const char *name, int32_t value)
     }
     if (strcmp(name, "skinny_parts") == 0) {
         g_tuning.skinny_parts = value;
+        return BCQ_OK;
+    }
+    if (strcmp(name, "skinny_version") == 0 && value <= 2) {
+        g_tuning.skinny_version = value;
+        return BCQ_OK;
+    }
+    if (strcmp(name, "skinny_lds_steps") == 0 && (value == 0 || value == 3 || value == 4)) {
+        g_tuning.skinny_lds_steps = value;
         return BCQ_OK;
     }
     if (strcmp(name, "probe") == 0 && value <= 1) {

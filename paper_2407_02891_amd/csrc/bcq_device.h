@@ -39,6 +39,28 @@ __device__ __forceinline__ void load_tile(TileRegs<Q, Z, SUB> &r, const uint8_t 
     for (int c = 0; c < (Q + Z) * SUB; ++c) r.scales[c] = __builtin_nontemporal_load(sp + c);
 }
 
+// dword 3 of a raw buffer descriptor (no swizzle, no stride, 32-bit data format)
+constexpr int kRawBufferFlags = 0x00020000;
+
+// The same tile through a buffer descriptor whose range is the tile (or empty): a load outside
+// the range returns zeros without touching memory.  Lets a loop request "the next tile, if any"
+// without a branch, so that the compiler can count the outstanding loads instead of draining them.
+template <int Q, int Z, int SUB>
+__device__ __forceinline__ void load_tile_buf(TileRegs<Q, Z, SUB> &r, __amdgpu_buffer_rsrc_t rsrc, int lane)
+{
+    constexpr int kNonTemporal = 2;
+    const uint32_t po = 16u * lane;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int i = 0; i < Q; ++i)
+            r.planes[t][i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, po + (t * Q + i) * 1024u, 0, kNonTemporal);
+    const uint32_t so = 2u * Q * 1024u + 4u * (Q + Z) * SUB * lane;
+#pragma unroll
+    for (int c = 0; c < (Q + Z) * SUB; ++c)
+        r.scales[c] = __builtin_amdgcn_raw_buffer_load_b32(rsrc, so + 4u * c, 0, kNonTemporal);
+}
+
 // binary16 bits of scale c (alpha_0..alpha_{Q-1}, then the offset) of row half t, byte range `range`
 template <int Q, int Z, int SUB>
 __device__ __forceinline__ uint32_t scale_bits_of(const TileRegs<Q, Z, SUB> &r, int t, int range, int c)

@@ -26,6 +26,9 @@ struct GemvTuning {
     int workgroups = 0; // grid size
     int waves = 0;      // waves per workgroup: 4 or 8
     int skinny_parts = 0;  // K split of the skinny kernel
+    int skinny_version = 0;    // 1 = the first skinny kernel (alpha folded into A) also where the second applies
+    int skinny_lds_steps = 0;  // second skinny kernel: MFMA steps per block whose A operand comes from the
+                               // LDS table, 3 or 4 (0 = automatic = 4)
     int probe = 0;      // timing experiment (wrong results): 1 = every tile re-reads tile 0
 #ifdef BCQ_TRACE
     unsigned long long *trace = nullptr;  // development builds: per-wave timestamps
@@ -35,7 +38,7 @@ hipError_t launch_gemv(const Geom &g, const void *packed, const uint16_t *x, uin
                        void *workspace, const GemvTuning &tuning, hipStream_t stream);
 // Single-pass kernel for 2 <= batch <= 16 (matrix cores); parts = K split, 0 = automatic.
 hipError_t launch_skinny(const Geom &g, const void *packed, const uint16_t *X, int ldx, uint16_t *Y, int ldy,
-                         int batch, void *workspace, int parts, hipStream_t stream);
+                         int batch, void *workspace, const GemvTuning &tuning, hipStream_t stream);
 hipError_t launch_read_probe(const void *buf, size_t bytes, void *sink, hipStream_t stream);
 
 constexpr int kProbeBlocks = 2048;

@@ -46,17 +46,34 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 constexpr int kXPitchBytes = 1040;  // 64 chunks x 16 B + 16 B: batch rows land in different banks
 constexpr int kXBufBytes = 16 * kXPitchBytes;
 
-// Loads (into registers) this thread's share of the X slice: 4 chunks of 8 activations.
-__device__ __forceinline__ void x_slice_load(const SkinnyParams &p, int slice, int tid, u32x4 (&xr)[4])
+// Loads (into registers) this thread's share of the X slice: 4 chunks of 8 activations.  X is read
+// through a buffer descriptor covering its batch rows; chunks that do not exist (batch column or
+// column out of range, or no such slice: `wanted` false) are given an out-of-range offset and
+// come back as zeros, so the loads are unconditional.
+__device__ __forceinline__ void x_slice_load(const SkinnyParams &p, __amdgpu_buffer_rsrc_t xrsrc, int slice, bool wanted,
+                                             int tid, u32x4 (&xr)[4])
 {
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         const int idx = tid + 256 * k, chunk = idx & 63, c = idx >> 6;
         const int col = slice * kTileCols + kChunkCols * chunk;
-        xr[k] = u32x4{0u, 0u, 0u, 0u};
-        if (c < p.batch && col < p.N)
-            xr[k] = *reinterpret_cast<const u32x4 *>(p.X + (size_t)c * p.ldx + col);
+        const bool ok = wanted && c < p.batch && col < p.N;
+        const uint32_t off = ok ? 2u * ((uint32_t)c * (uint32_t)p.ldx + (uint32_t)col) : 0xfffffff0u;
+        xr[k] = __builtin_amdgcn_raw_buffer_load_b128(xrsrc, off, 0, 0);
     }
+}
+
+// Descriptor of the activations: rows 0 .. batch-1 of X (batch * ldx binary16 values).
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t x_descriptor(const SkinnyParams &p)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(p.X), 0, (int)(2u * (uint32_t)p.batch * (uint32_t)p.ldx),
+                                             kRawBufferFlags);
+}
+
+// Descriptor of one tile, or an empty one.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t tile_descriptor(const uint8_t *tile, unsigned tile_bytes, bool wanted)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t *>(tile), 0, wanted ? (int)tile_bytes : 0, kRawBufferFlags);
 }
 
 // Stores them to LDS, elements reordered to (0,4,1,5,2,6,3,7) within a chunk.
@@ -142,12 +159,65 @@ __device__ __forceinline__ uint32_t scale_bits(const TileRegs<Q, Z, SUB> &t, int
     return v;
 }
 
+// Adds the wave's partial results to the outputs.  On entry acc[t][i] = partial of row
+// 32*tile + 16*t + 4*h + i for batch column r (the MFMA accumulator layout, lane = 16h + r).  The
+// 32 x 16 block is first turned through LDS (`stage`, private to the wave, kStageFloats floats) so
+// that lanes 0..31 and 32..63 each hold 32 consecutive rows of one batch column: a store or atomic
+// instruction then covers whole 64-byte lines of Y / of the accumulator words instead of
+// scattered 8-byte pieces.  With one K part the values are stored directly; otherwise the parts
+// are combined with the fixed-point split-K atomics (see bcq_device.h).
+constexpr int kStagePitch = 33;
+constexpr int kStageFloats = 17 * kStagePitch;
+
+__device__ __forceinline__ void skinny_store(const SkinnyParams &p, const f32x4 (&acc)[2], int tile, int lane,
+                                             float *stage)
+{
+    const int r = lane & 15, h = lane >> 4;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) stage[r * kStagePitch + 16 * t + 4 * h + i] = acc[t][i];
+    // same wave: its LDS operations complete in order, no barrier needed
+    const int row = tile * kTileRows + (lane & 31), half = lane >> 5;
+    float v[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) v[k] = stage[(2 * k + half) * kStagePitch + (lane & 31)];
+    if (p.parts == 1) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int col = 2 * k + half;
+            if (col < p.batch && row < p.M) p.Y[(size_t)col * p.ldy + row] = float_to_half_bits(v[k]);
+        }
+        return;
+    }
+    unsigned long long mine[8], old[8];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        const int col = 2 * k + half;
+        mine[k] = encode_partial(v[k]);
+        old[k] = 0;
+        if (col < p.batch)
+            old[k] = __hip_atomic_fetch_add(p.accum + (size_t)col * p.Mp + row, mine[k], __ATOMIC_RELAXED,
+                                            __HIP_MEMORY_SCOPE_AGENT);
+    }
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        const int col = 2 * k + half;
+        const unsigned long long total = old[k] + mine[k];
+        if (col < p.batch && arrivals_of(total) == (unsigned)p.parts) {
+            if (row < p.M) p.Y[(size_t)col * p.ldy + row] = float_to_half_bits(decode_total(total));
+            __hip_atomic_store(p.accum + (size_t)col * p.Mp + row, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+}
+
 template <int Q, int Z, int SUB>
 __global__ __launch_bounds__(256) void bcq_skinny_kernel(SkinnyParams p)
 {
     __shared__ __attribute__((aligned(16))) uint8_t xs[2 * kXBufBytes];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: tile pointers stay in SGPRs
     const int tg = blockIdx.x % p.ntg, part = blockIdx.x / p.ntg;
     const int tile = 4 * tg + wave;
     const bool active = tile < p.ntile;
@@ -157,11 +227,12 @@ __global__ __launch_bounds__(256) void bcq_skinny_kernel(SkinnyParams p)
     const size_t slice_stride = (size_t)p.ntile * p.tile_bytes;
     const uint8_t *tile_ptr = p.blob + ((size_t)s_begin * p.ntile + (active ? tile : 0)) * p.tile_bytes;
 
+    const __amdgpu_buffer_rsrc_t xrsrc = x_descriptor(p);
     TileRegs<Q, Z, SUB> cur;
-    if (active && s_begin < s_end) load_tile<Q, Z, SUB>(cur, tile_ptr, lane);
+    load_tile_buf<Q, Z, SUB>(cur, tile_descriptor(tile_ptr, p.tile_bytes, active && s_begin < s_end), lane);
     {
         u32x4 xr[4];
-        x_slice_load(p, s_begin, tid, xr);
+        x_slice_load(p, xrsrc, s_begin, true, tid, xr);
         x_slice_store(xs, tid, xr);
     }
     __syncthreads();
@@ -173,10 +244,10 @@ __global__ __launch_bounds__(256) void bcq_skinny_kernel(SkinnyParams p)
         TileRegs<Q, Z, SUB> nxt;
         u32x4 xr[4];
         tile_ptr += slice_stride;
-        if (more) {
-            if (active) load_tile<Q, Z, SUB>(nxt, tile_ptr, lane);
-            x_slice_load(p, slice + 1, tid, xr);
-        }
+        // unconditional requests for the next slice (empty descriptor / out-of-range offsets when
+        // there is none): they stay in flight while this slice is computed
+        load_tile_buf<Q, Z, SUB>(nxt, tile_descriptor(tile_ptr, p.tile_bytes, more && active), lane);
+        x_slice_load(p, xrsrc, slice + 1, more, tid, xr);
         if (active) {
             // per (row half, plane): un-rotate, fold the sign of alpha into the bits, |alpha| pair
             uint32_t abs_pair[2][Q][SUB];
@@ -254,41 +325,178 @@ __global__ __launch_bounds__(256) void bcq_skinny_kernel(SkinnyParams p)
     }
 
     if (!active) return;
-    // acc[t][i] = partial of row 32*tile + 16*t + 4*h + i for batch column r
-    const int col = r;
-    if (col >= p.batch) return;
-    if (p.parts == 1) {
-#pragma unroll
-        for (int t = 0; t < 2; ++t)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int row = tile * kTileRows + 16 * t + 4 * h + i;
-                if (row < p.M) p.Y[(size_t)col * p.ldy + row] = float_to_half_bits(acc[t][i]);
-            }
-        return;
+    // the X buffers are free after the loop's last barrier: each wave stages its block there
+    skinny_store(p, acc, tile, lane, reinterpret_cast<float *>(xs) + wave * kStageFloats);
+}
+
+// ---------------------------------------------------------------------------------
+// Second version of the kernel, for one scaling group per 128-column block (group a multiple
+// of 128, or the whole row).  The first version spends nearly all its time in the vector ALU
+// turning sign bits into +-alpha operands (9 operations per 8 signs).  Two changes cut that:
+//
+//  * The four lanes (h = 0..3) that hold the four blocks of one row exchange dwords (a 4 x 4
+//    transpose with v_permlane16_swap / v_permlane32_swap), after which lane (h, r) holds, for
+//    EVERY block B of row r, the chunks 4h..4h+3.  One MFMA step then contracts 32 columns of a
+//    single block, so alpha no longer has to be folded into A: A is just +-1.0, the products of
+//    one block are collected in a temporary accumulator and scaled by alpha (fp32) when the
+//    block is done.  The scales are fetched into the accumulator's row layout with ds_bpermute.
+//  * +-1.0 operands do not depend on the row, so most of them come from a 256-entry table in
+//    LDS (one ds_read_b128 per 8 signs, 8 interleaved copies so that any 8 neighbouring lanes
+//    read different banks); the rest are still expanded in registers, which keeps the LDS pipe
+//    and the vector ALU about equally busy.  LDS_STEPS of the 4 MFMA steps of a block use the table.
+//
+// The offset term uses A = all ones: the block's column sums of X, scaled by z afterwards.
+constexpr int kTabCopies = 8;
+constexpr int kTabBytes = 256 * kTabCopies * 16;  // 32 KB
+
+template <int Q, int Z, int LDS_STEPS>
+__global__ __launch_bounds__(256) void bcq_skinny2_kernel(SkinnyParams p)
+{
+    __shared__ __attribute__((aligned(16))) uint8_t xs[2 * kXBufBytes];
+    __shared__ __attribute__((aligned(16))) uint8_t tab[kTabBytes];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: tile pointers stay in SGPRs
+    const int tg = blockIdx.x % p.ntg, part = blockIdx.x / p.ntg;
+    const int tile = 4 * tg + wave;
+    const bool active = tile < p.ntile;
+    const int s_begin = (int)(((long long)part * p.nslice) / p.parts);
+    const int s_end = (int)(((long long)(part + 1) * p.nslice) / p.parts);
+    const int r = lane & 15, h = lane >> 4;
+    const size_t slice_stride = (size_t)p.ntile * p.tile_bytes;
+    const uint8_t *tile_ptr = p.blob + ((size_t)s_begin * p.ntile + (active ? tile : 0)) * p.tile_bytes;
+
+    const __amdgpu_buffer_rsrc_t xrsrc = x_descriptor(p);
+    TileRegs<Q, Z, 1> cur;
+    load_tile_buf<Q, Z, 1>(cur, tile_descriptor(tile_ptr, p.tile_bytes, active && s_begin < s_end), lane);
+    {
+        u32x4 xr[4];
+        x_slice_load(p, xrsrc, s_begin, true, tid, xr);
+        x_slice_store(xs, tid, xr);
     }
-    unsigned long long mine[8], old[8];
+    // Sign table: entry b holds 8 binary16 values, pair d = (bit d, bit d + 4) of b, +1.0 for a set
+    // bit (the element order the staged X uses); copy c of entry b sits at (8 b + c) * 16.
 #pragma unroll
-    for (int t = 0; t < 2; ++t)
+    for (int k = 0; k < 8; ++k) {
+        const int idx = tid + 256 * k, b = idx >> 3;
+        u32x4 e;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int row = tile * kTileRows + 16 * t + 4 * h + i;
-            mine[4 * t + i] = encode_partial(acc[t][i]);
-            old[4 * t + i] = __hip_atomic_fetch_add(p.accum + (size_t)col * p.Mp + row, mine[4 * t + i],
-                                                    __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
+        for (int d = 0; d < 4; ++d)
+            e[d] = (((b >> d) & 1) ? 0x3c00u : 0xbc00u) | ((((b >> (d + 4)) & 1) ? 0x3c00u : 0xbc00u) << 16);
+        *reinterpret_cast<u32x4 *>(tab + idx * 16) = e;
+    }
+    __syncthreads();
+    const uint8_t *my_tab = tab + (lane & (kTabCopies - 1)) * 16;
+
+    f32x4 acc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+    const u32x4 ones = {0x3c003c00u, 0x3c003c00u, 0x3c003c00u, 0x3c003c00u};
+
+    for (int slice = s_begin; slice < s_end; ++slice) {
+        const bool more = slice + 1 < s_end;
+        TileRegs<Q, Z, 1> nxt;
+        u32x4 xr[4];
+        tile_ptr += slice_stride;
+        // unconditional requests for the next slice (empty descriptor / out-of-range offsets when
+        // there is none): they stay in flight while this slice is computed
+        load_tile_buf<Q, Z, 1>(nxt, tile_descriptor(tile_ptr, p.tile_bytes, more && active), lane);
+        x_slice_load(p, xrsrc, slice + 1, more, tid, xr);
+        if (active) {
+            // chunk order, then the 4 x 4 dword transpose across the lanes r, r+16, r+32, r+48:
+            // wb[t][i][B] = chunks 4h .. 4h+3 of (row 16t + r, block B, plane i)
+            uint32_t wb[2][Q][4];
 #pragma unroll
-    for (int t = 0; t < 2; ++t)
+            for (int t = 0; t < 2; ++t)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int row = tile * kTileRows + 16 * t + 4 * h + i;
-            const unsigned long long total = old[4 * t + i] + mine[4 * t + i];
-            if (arrivals_of(total) == (unsigned)p.parts) {
-                if (row < p.M) p.Y[(size_t)col * p.ldy + row] = float_to_half_bits(decode_total(total));
-                __hip_atomic_store(p.accum + (size_t)col * p.Mp + row, 0ull, __ATOMIC_RELAXED,
-                                   __HIP_MEMORY_SCOPE_AGENT);
+                for (int i = 0; i < Q; ++i) {
+                    u32x4 w = cur.planes[t][i];
+                    unrotate<1>(w, r);
+                    const auto e01 = __builtin_amdgcn_permlane16_swap(w.x, w.y, false, false);
+                    const auto e23 = __builtin_amdgcn_permlane16_swap(w.z, w.w, false, false);
+                    const auto f02 = __builtin_amdgcn_permlane32_swap(e01[0], e23[0], false, false);
+                    const auto f13 = __builtin_amdgcn_permlane32_swap(e01[1], e23[1], false, false);
+                    wb[t][i][0] = f02[0]; wb[t][i][1] = f13[0]; wb[t][i][2] = f02[1]; wb[t][i][3] = f13[1];
+                }
+            const uint8_t *xb = xs + (slice - s_begin & 1) * kXBufBytes + r * kXPitchBytes + h * 64;
+            // The 16 MFMA steps (block B = step / 4, chunk group s = step % 4) are software-pipelined:
+            // the operands of step k+1 are requested from LDS before the MFMAs of step k are issued.
+            auto fetch = [&](int step, f16x8 (&a)[2][Q], f16x8 &bx) {
+                const int B = step >> 2, s = step & 3;
+                bx = *reinterpret_cast<const f16x8 *>(xb + (16 * B + s) * 16);
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+#pragma unroll
+                    for (int i = 0; i < Q; ++i) {
+                        const uint32_t w = wb[t][i][B];
+                        if (s < LDS_STEPS) {
+                            const uint32_t byte = (w >> (8 * s)) & 0xffu;
+                            a[t][i] = *reinterpret_cast<const f16x8 *>(my_tab + byte * (16 * kTabCopies));
+                        } else {
+                            const uint32_t wn = ~w, wn4 = wn >> 4;
+                            if (s == 0) a[t][i] = expand_byte<0>(wn, wn4, 0x3c003c00u);
+                            if (s == 1) a[t][i] = expand_byte<1>(wn, wn4, 0x3c003c00u);
+                            if (s == 2) a[t][i] = expand_byte<2>(wn, wn4, 0x3c003c00u);
+                            if (s == 3) a[t][i] = expand_byte<3>(wn, wn4, 0x3c003c00u);
+                        }
+                    }
+            };
+            f16x8 abuf[2][2][Q], bbuf[2];
+            fetch(0, abuf[0], bbuf[0]);
+            f32x4 C[2][Q];
+            f32x4 Cz = {0.f, 0.f, 0.f, 0.f};
+            uint32_t sc[4][Q + Z];
+#pragma unroll
+            for (int step = 0; step < 16; ++step) {
+                const int B = step >> 2, s = step & 3, cb = step & 1;
+                if (step + 1 < 16) fetch(step + 1, abuf[cb ^ 1], bbuf[cb ^ 1]);
+                if (s == 0) {
+                    // scales of rows 4h + j of this block, held by lanes 16 B + 4h + j, into this lane
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+#pragma unroll
+                        for (int e = 0; e < Q + Z; ++e)
+                            sc[j][e] = (uint32_t)__builtin_amdgcn_ds_bpermute(4 * (16 * B + 4 * h + j), (int)cur.scales[e]);
+#pragma unroll
+                    for (int t = 0; t < 2; ++t)
+#pragma unroll
+                        for (int i = 0; i < Q; ++i) C[t][i] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    Cz = f32x4{0.f, 0.f, 0.f, 0.f};
+                }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+#pragma unroll
+                    for (int i = 0; i < Q; ++i)
+                        C[t][i] = __builtin_amdgcn_mfma_f32_16x16x32_f16(abuf[cb][t][i], bbuf[cb], C[t][i], 0, 0, 0);
+                if (Z)
+                    Cz = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, ones), bbuf[cb], Cz, 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                if (s == 3) {
+                    // acc[t][j] += alpha_i(row 16t + 4h + j, block B) * C[t][i][j]  (+ z * column sums)
+#pragma unroll
+                    for (int t = 0; t < 2; ++t)
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+#pragma unroll
+                            for (int c = 0; c < Q + Z; ++c) {
+                                const int e = t * (Q + Z) + c;  // half index in the lane's scale record
+                                const uint32_t pair = sc[j][e >> 1];
+                                const float v = half_bits_to_float((e & 1) ? (pair >> 16) : (pair & 0xffffu));
+                                acc[t][j] = fmaf(v, c < Q ? C[t][c < Q ? c : 0][j] : Cz[j], acc[t][j]);
+                            }
+                        }
+                }
             }
         }
+        if (more) {
+            x_slice_store(xs + (slice + 1 - s_begin & 1) * kXBufBytes, tid, xr);
+            if (active) cur = nxt;
+        }
+        __syncthreads();  // next X slice written, everyone done reading the current one
+    }
+
+    if (!active) return;
+    // the X buffers are free after the loop's last barrier: each wave stages its block there
+    skinny_store(p, acc, tile, lane, reinterpret_cast<float *>(xs) + wave * kStageFloats);
 }
 
 // ---------------------------------------------------------------------------------
@@ -311,17 +519,29 @@ static hipError_t launch_skinny_one(const SkinnyParams &p, hipStream_t stream)
     return hipGetLastError();
 }
 
+template <int Q, int Z, int LDS_STEPS>
+static hipError_t launch_skinny2_one(const SkinnyParams &p, hipStream_t stream)
+{
+    hipLaunchKernelGGL((bcq_skinny2_kernel<Q, Z, LDS_STEPS>), dim3((unsigned)(p.ntg * p.parts)), dim3(256), 0, stream,
+                       p);
+    return hipGetLastError();
+}
+
 template <int Q, int Z>
-static hipError_t launch_skinny_qz(const SkinnyParams &p, int sub, hipStream_t stream)
+static hipError_t launch_skinny_qz(const SkinnyParams &p, int sub, int version, int lds_steps, hipStream_t stream)
 {
     if (sub == 2) return launch_skinny_one<Q, Z, 2>(p, stream);
     if (sub == 4) return launch_skinny_one<Q, Z, 4>(p, stream);
-    return launch_skinny_one<Q, Z, 1>(p, stream);
+    if (version == 1) return launch_skinny_one<Q, Z, 1>(p, stream);
+    // all four MFMA steps of a block from the LDS table measured fastest; 3 (one step expanded in
+    // registers) is kept as the alternative for tuning runs
+    return lds_steps == 3 ? launch_skinny2_one<Q, Z, 3>(p, stream) : launch_skinny2_one<Q, Z, 4>(p, stream);
 }
 
 hipError_t launch_skinny(const Geom &g, const void *packed, const uint16_t *X, int ldx, uint16_t *Y, int ldy,
-                         int batch, void *workspace, int parts, hipStream_t stream)
+                         int batch, void *workspace, const GemvTuning &tuning, hipStream_t stream)
 {
+    const int parts = tuning.skinny_parts;
     SkinnyParams p;
     p.blob = static_cast<const uint8_t *>(packed);
     p.X = X; p.Y = Y;
@@ -333,14 +553,14 @@ hipError_t launch_skinny(const Geom &g, const void *packed, const uint16_t *X, i
     if (!workspace) p.parts = 1;  // only reachable for a single column slice
     p.tile_bytes = g.tile_bytes;
     switch (g.q * 2 + g.z) {
-        case 2: return launch_skinny_qz<1, 0>(p, g.sub, stream);
-        case 3: return launch_skinny_qz<1, 1>(p, g.sub, stream);
-        case 4: return launch_skinny_qz<2, 0>(p, g.sub, stream);
-        case 5: return launch_skinny_qz<2, 1>(p, g.sub, stream);
-        case 6: return launch_skinny_qz<3, 0>(p, g.sub, stream);
-        case 7: return launch_skinny_qz<3, 1>(p, g.sub, stream);
-        case 8: return launch_skinny_qz<4, 0>(p, g.sub, stream);
-        case 9: return launch_skinny_qz<4, 1>(p, g.sub, stream);
+        case 2: return launch_skinny_qz<1, 0>(p, g.sub, tuning.skinny_version, tuning.skinny_lds_steps, stream);
+        case 3: return launch_skinny_qz<1, 1>(p, g.sub, tuning.skinny_version, tuning.skinny_lds_steps, stream);
+        case 4: return launch_skinny_qz<2, 0>(p, g.sub, tuning.skinny_version, tuning.skinny_lds_steps, stream);
+        case 5: return launch_skinny_qz<2, 1>(p, g.sub, tuning.skinny_version, tuning.skinny_lds_steps, stream);
+        case 6: return launch_skinny_qz<3, 0>(p, g.sub, tuning.skinny_version, tuning.skinny_lds_steps, stream);
+        case 7: return launch_skinny_qz<3, 1>(p, g.sub, tuning.skinny_version, tuning.skinny_lds_steps, stream);
+        case 8: return launch_skinny_qz<4, 0>(p, g.sub, tuning.skinny_version, tuning.skinny_lds_steps, stream);
+        case 9: return launch_skinny_qz<4, 1>(p, g.sub, tuning.skinny_version, tuning.skinny_lds_steps, stream);
     }
     return hipErrorInvalidValue;
 }

@@ -227,3 +227,21 @@ def test_pack_rows_builds_the_same_blob_as_one_pack(group, offset):
     assert torch.equal(fused.packed, whole.packed)
     y = U.gpu_gemv(fused, U.x_dev(L))
     U.gate(y[None, :], ref.gemm(L.planes, L.alpha, L.offset, L.x), "fused rows")
+
+
+@pytest.mark.parametrize("option,value", [("skinny_version", 1), ("skinny_version", 2), ("skinny_lds_steps", 3)])
+@pytest.mark.parametrize("q,offset", [(3, False), (2, True), (4, True)])
+def test_skinny_kernel_variants(option, value, q, offset):
+    """Both skinny kernels (alpha folded into the matrix-core operand / +-1 operands from the LDS
+    table with alpha applied to the accumulators) and the table/register split of the second,
+    on ragged shapes, a multi-part K split and an odd batch."""
+    try:
+        bcq.set_option(option, value)
+        _run_case(203, 3200, q, 128, offset, batch=7, seed=q + value)
+        _run_case(64, 1024, q, 256, offset, batch=16, seed=q + value + 1)
+        L = bcq_synth.make_exact_layer(96, 2048, q, group=128, offset=offset, batch=3, seed=50 + q)
+        pl = U.upload_and_pack(L, max_batch=3)
+        expect = ref.gemm(L.planes, L.alpha, L.offset, L.x).astype(np.float16).astype(np.float64)
+        assert np.array_equal(U.gpu_gemm(pl, U.x_dev(L)).astype(np.float64), expect)
+    finally:
+        bcq.set_option(option, 0)
