@@ -188,15 +188,17 @@ def main():
     dom = per_layer[DOMINANT]
     achieved = dom["weight_bytes"] / (dom["us_per_gemv"] * 1e-6) / 1e9
     if B > 1:
-        # The single-pass skinny kernel is bound by the vector ALU work of expanding sign bits into
-        # binary16 operands for the matrix cores: 9 lane-operations per 8 signs.  Peak = 256 CUs x 4
-        # SIMDs x 16 lanes x 2.4 GHz = 39.3 T lane-op/s.
-        lane_ops = 9.0 / 8.0 * Q * dom["M"] * dom["N"]
-        alu = lane_ops / (dom["us_per_gemv"] * 1e-6) / 1e12
-        roofline = dict(bound="alu", kernel="bcq_skinny_kernel (q=%d, no offset, group 128, batch %d) on %dx%d"
-                                            % (Q, B, dom["M"], dom["N"]),
-                        achieved=round(alu, 2), peak=39.3, unit="T lane-op/s", frac=round(alu / 39.3, 4),
-                        lane_ops_per_launch=lane_ops, us_per_launch=dom["us_per_gemv"], traffic=None,
+        # The single-pass skinny kernel contracts on the matrix cores (binary16 in, fp32 accumulate):
+        # useful work 2 * q * M * N * batch flop per launch against the dense fp16 MFMA peak.  What
+        # actually limits it is turning every sign into a binary16 operand (LDS table reads), which
+        # costs the same for any batch up to 16 -- hence the low fraction at small batch.
+        flop = 2.0 * Q * dom["M"] * dom["N"] * B
+        tfl = flop / (dom["us_per_gemv"] * 1e-6) / 1e12
+        roofline = dict(bound="mfma", kernel="bcq_skinny2_kernel (q=%d, no offset, group 128, batch %d) on %dx%d"
+                                             % (Q, B, dom["M"], dom["N"]),
+                        achieved=round(tfl, 2), peak=2500.0, unit="TFLOP/s", frac=round(tfl / 2500.0, 4),
+                        flop_per_launch=flop, us_per_launch=dom["us_per_gemv"], traffic=None,
+                        limiter="LDS read bandwidth of the sign-expansion table (see DESIGN.md 6.4)",
                         weight_GBps=dom["weight_GBps"])
     else:
         roofline = dict(bound="hbm",
