@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the binary-coding GEMV (inference path of GPTQT) on one MI355X.
 
-Default workload (benchmark configs[1]): the OPT-30B-shaped 3-bit layer set at
+Default workload: the OPT-30B-shaped 3-bit layer set at
 batch 1 -- 7168x7168 (attention projection), 28672x7168 (fc1), 7168x28672 (fc2),
 q = 3, group 128, no offset, synthetic seeded inputs (bcq_synth).  One "step" is
 one pass over the layers, one bcq_gemv each, on one stream.  Weights are
@@ -9,12 +9,12 @@ resident in HBM before timing; every step reads a different copy of the packed
 weights (the copies total > 1 GiB) so that neither L2 nor the 256 MB memory-side
 cache serves them.
 
-Other workloads (--workload): `llama70b_block` = configs[4], the seven GEMVs of a
+Other workloads (--workload): `llama70b_block` = the seven GEMVs of a
 Llama-2-70B-shaped decoder block in sequence; `llama70b_block_fused` = the same
 weights with the projections that share their input (q/k/v; gate/up) packed into
 one blob each with bcq_pack_rows, four GEMVs per step.  --q selects 2 or 3 planes.
 
-Prints ONE JSON line (see README for the fields).  `value` is the
+Prints ONE JSON line (the fields are described in README.md).  `value` is the
 effective weight bandwidth of the whole step; `roofline` is for the dominant
 kernel (the 7168x28672 GEMV) from its own timed region; `cpu_baseline` is the
 fp64 oracle on the host cores for the same layer set.
@@ -198,7 +198,7 @@ def main():
                                              % (Q, B, dom["M"], dom["N"]),
                         achieved=round(tfl, 2), peak=2500.0, unit="TFLOP/s", frac=round(tfl / 2500.0, 4),
                         flop_per_launch=flop, us_per_launch=dom["us_per_gemv"], traffic=None,
-                        limiter="LDS read bandwidth of the sign-expansion table (see DESIGN.md 6.4)",
+                        limiter="LDS read bandwidth of the sign-expansion table",
                         weight_GBps=dom["weight_GBps"])
     else:
         roofline = dict(bound="hbm",
