@@ -36,6 +36,9 @@ WORKLOADS = {
     "opt30b": ([("attn_proj", [("attn_proj", 7168)], 7168), ("fc1", [("fc1", 28672)], 7168),
                 ("fc2", [("fc2", 7168)], 28672)], "fc2",
                "OPT-30B-shaped layer set (7168x7168, 28672x7168, 7168x28672)"),
+    "opt66b": ([("attn_proj", [("attn_proj", 9216)], 9216), ("fc1", [("fc1", 36864)], 9216),
+                ("fc2", [("fc2", 9216)], 36864)], "fc2",
+               "OPT-66B-shaped layer set (9216x9216, 36864x9216, 9216x36864)"),
     "llama70b_block": ([("q", [("q", 8192)], 8192), ("k", [("k", 1024)], 8192), ("v", [("v", 1024)], 8192),
                         ("o", [("o", 8192)], 8192), ("gate", [("gate", 28672)], 8192),
                         ("up", [("up", 28672)], 8192), ("down", [("down", 8192)], 28672)], "down",
@@ -57,6 +60,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=12)
     ap.add_argument("--workload", choices=sorted(WORKLOADS), default="opt30b")
     ap.add_argument("--q", type=int, choices=(2, 3), default=3, help="number of sign planes")
+    ap.add_argument("--offset", action="store_true", help="add the per-group fp16 offset term (N(0, 0.01))")
+    ap.add_argument("--outliers", action="store_true", help="scale 1 %% of the activation channels by 20")
     ap.add_argument("--batch", type=int, default=1,
                     help="activation vectors per call: 1 = bcq_gemv (the headline), 2..16 = bcq_gemm_skinny")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing leg")
@@ -98,15 +103,17 @@ def main():
     total_bytes = 0
     for name, parts, N in LAUNCHES:
         M = sum(rows for _, rows in parts)
-        pl = bcq.PackedLayer(M, N, Q, GROUP, False, max_batch=B)
+        pl = bcq.PackedLayer(M, N, Q, GROUP, args.offset, max_batch=B)
         subs, row0, nbytes = [], 0, 0
         for k, (pname, rows) in enumerate(parts):  # each projection from its own tensors
-            L = bcq_synth.make_layer(rows, N, Q, group=GROUP, offset=False, batch=B, seed=k)
+            L = bcq_synth.make_layer(rows, N, Q, group=GROUP, offset=args.offset, batch=B, seed=k,
+                                     outlier_frac=0.01 if args.outliers else 0.0)
             codes = to_dev(L.codes())
             alpha = to_dev(L.alpha.view(np.uint16).astype(np.int16)).view(torch.float16)
-            pl.pack_rows_from(row0, codes, alpha, None)
+            off = to_dev(L.offset.view(np.uint16).astype(np.int16)).view(torch.float16) if args.offset else None
+            pl.pack_rows_from(row0, codes, alpha, off)
             torch.cuda.synchronize()
-            del codes, alpha
+            del codes, alpha, off
             subs.append((row0, L))
             row0 += rows
             nbytes += L.weight_bytes()
@@ -194,21 +201,22 @@ def main():
         # costs the same for any batch up to 16 -- hence the low fraction at small batch.
         flop = 2.0 * Q * dom["M"] * dom["N"] * B
         tfl = flop / (dom["us_per_gemv"] * 1e-6) / 1e12
-        roofline = dict(bound="mfma", kernel="bcq_skinny2_kernel (q=%d, no offset, group 128, batch %d) on %dx%d"
-                                             % (Q, B, dom["M"], dom["N"]),
+        roofline = dict(bound="mfma", kernel="bcq_skinny2_kernel (q=%d, %s, group 128, batch %d) on %dx%d"
+                                             % (Q, "offset" if args.offset else "no offset", B, dom["M"], dom["N"]),
                         achieved=round(tfl, 2), peak=2500.0, unit="TFLOP/s", frac=round(tfl / 2500.0, 4),
                         flop_per_launch=flop, us_per_launch=dom["us_per_gemv"], traffic=None,
                         limiter="LDS read bandwidth of the sign-expansion table",
                         weight_GBps=dom["weight_GBps"])
     else:
         roofline = dict(bound="hbm",
-                        kernel="bcq_gemv_kernel (q=%d, no offset, group 128) on %dx%d" % (Q, dom["M"], dom["N"]),
+                        kernel="bcq_gemv_kernel (q=%d, %s, group 128) on %dx%d"
+                               % (Q, "offset" if args.offset else "no offset", dom["M"], dom["N"]),
                         achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s",
                         frac=round(achieved / HBM_PEAK_GBS, 4), bytes_per_launch=dom["weight_bytes"],
                         us_per_launch=dom["us_per_gemv"], traffic=None)
     # HBM bytes per launch measured separately with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE); see profiles/
     traffic_file = os.path.join(ROOT, "profiles", "bcq_gemv_opt30b_q3_hbm_traffic.md")
-    if os.path.exists(traffic_file) and args.workload == "opt30b" and Q == 3 and B == 1:
+    if os.path.exists(traffic_file) and args.workload == "opt30b" and Q == 3 and B == 1 and not args.offset:
         for line in open(traffic_file):
             if line.startswith("hbm_bytes_per_launch_fc2"):
                 roofline["traffic"] = float(line.split("=")[1])
@@ -224,7 +232,7 @@ def main():
             x0 = layers[name]["subs"][0][1].x  # the activations every part of this launch was given
             y_all = layers[name]["y"].cpu().numpy().astype(np.float64)
             for row0, L in layers[name]["subs"]:
-                y_ref = ref.gemm(L.planes, L.alpha, None, x0)
+                y_ref = ref.gemm(L.planes, L.alpha, L.offset, x0)
                 y_gpu = y_all[:, row0:row0 + L.M]
                 rms = math.sqrt(float(np.mean(y_ref ** 2)))
                 err = np.abs(y_gpu - y_ref) / np.maximum(np.abs(y_ref), rms / 64.0)
@@ -240,8 +248,9 @@ def main():
         "value": round(value_gbs, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16 activations, 1-bit planes x%d, f32 accumulate" % Q, "data": "synthetic",
-        "config": {"workload": "%s, q=%d, group=128, batch=%d, cold weights (%d rotating copies)"
-                               % (WORKLOAD_TEXT, Q, B, n_copies), "launches_per_step": len(LAYERS),
+        "config": {"workload": "%s, q=%d, group=128%s%s, batch=%d, cold weights (%d rotating copies)"
+                               % (WORKLOAD_TEXT, Q, ", with offset" if args.offset else "",
+                                  ", outlier channels" if args.outliers else "", B, n_copies), "launches_per_step": len(LAYERS),
                    "weight_bytes_per_step": total_bytes, "launch": "graph" if not args.no_graph else "eager"},
         "pct_of_hbm_peak": round(value_gbs / HBM_PEAK_GBS * 100, 2),
         "layers": per_layer, "roofline": roofline, "cpu_baseline": cpu, "parity": parity,

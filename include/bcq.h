@@ -182,7 +182,7 @@ bcq_status bcq_read_probe(const void *buf, size_t bytes, void *sink, void *strea
 
 /*
  * Launch-shape overrides for tuning runs (HOST state, process-wide, not
- * thread-safe).  Names: "workgroups" (grid size of the GEMV), "waves"
+ * thread-safe).  Names: "workgroups" (grid size of the GEMV and of the skinny kernel), "waves"
  * (waves per workgroup, 4 or 8), "skinny_parts" (K split of bcq_gemm_skinny for
  * batch >= 2), "skinny_version" (1 = the kernel that folds alpha into the
  * matrix-core operand, 2 = the kernel that takes +-1 operands from an LDS table;

@@ -3,28 +3,42 @@
 //
 // With several activation vectors the work per weight bit grows with the batch while the
 // bytes do not, so the path stops being HBM-bound and the sign-sum tables of the batch-1
-// kernel (one table set per activation vector) no longer fit in LDS.  Here the planes are
-// instead expanded in registers to binary16 values +-alpha and contracted with the
-// activations on the matrix cores (v_mfma_f32_16x16x32_f16, fp32 accumulate): the cost is
-// the same for every batch up to 16.
+// kernel (one table set per activation vector) no longer fit in LDS.  Here every sign becomes
+// a binary16 operand of the matrix cores (v_mfma_f32_16x16x32_f16, fp32 accumulate); the cost
+// is the same for every batch up to 16.
 //
-//  * Same packed blob as the GEMV (bcq_layout.h).  A wave owns one 32-row tile and walks over
-//    the column slices of its K-part; lane l = 16h + r holds, per row half t and plane i, the
-//    128 sign bits of (row 16t + r, 128-column block h) -- exactly the A-operand ownership of
-//    the MFMA (row = l mod 16, k-octet = l div 16).  The GEMV's per-row byte rotation is undone
-//    once per 128 bits (a dword rotate and a funnel shift).
-//  * One MFMA step contracts chunk s (8 columns) of all four blocks: A = 8 binary16 values
-//    (sign ? +alpha : -alpha) built from one byte of sign bits with 1 v_perm_b32 + 4 x
-//    (shift, and-or); B = the 8 activations of that chunk for batch column l mod 16, one
-//    ds_read_b128 from a staged copy of X (pitch 1040 B: conflict-free).  alpha is folded into A
-//    because the four k-octets of one MFMA belong to four different scaling groups.
-//    The pairing inside an octet (elements 2d, 2d+1 <-> columns d, d+4) is arbitrary as long
-//    as A and B agree; X is stored in LDS in that order.
-//  * The offset term of Eq. 11 is one more MFMA per chunk with A = (z, z, ..., z).
-//  * The four waves of a workgroup work on four adjacent row tiles and share the staged X
-//    slice (double-buffered, one barrier per slice).
-//  * K is split into `parts` so that ~2000 waves exist; the parts are combined with the same
-//    fixed-point 64-bit atomics as in the GEMV (one per output element and part).
+// Common skeleton (bcq_skinny_kernel<Q, Z, SUB, VER, LDS_STEPS>):
+//  * Same packed blob as the GEMV (bcq_layout.h).  A work unit is (tile group, column slice): the
+//    four waves of a workgroup take the four row tiles of the group and share an LDS copy of the
+//    slice of X (pitch 1040 B: conflict-free ds_read_b128; double-buffered, one barrier per unit).
+//    The units, ordered tile group first, are cut into equal contiguous ranges, one per workgroup,
+//    with as many workgroups as the chip holds at once: every workgroup does the same number of
+//    units (+-1) whatever the shape.  When a range leaves a tile group the accumulators are
+//    flushed; the workgroups that share a tile group are combined with the same fixed-point 64-bit
+//    atomics as in the GEMV (the expected number of arrivals follows from the ranges).
+//  * Tile and X loads go through buffer descriptors (empty / out of range when there is no next
+//    unit) so that the loop has no branch around them and the compiler counts outstanding loads.
+//  * Before the flush the 32 x 16 result block of a wave is turned through LDS so that a store or
+//    atomic instruction covers whole 64-byte lines.
+//
+// Two ways to form the A operand:
+//  VER 1 (any group size): lane l = 16h + r holds the 128 sign bits of (row r, block h, plane i)
+//    -- exactly the A-operand ownership of the MFMA (row = l mod 16, k-octet = l div 16) -- so one
+//    MFMA step mixes four blocks, i.e. four scaling groups, and alpha is folded into A: one byte
+//    of signs -> 8 values +-alpha with 1 v_perm_b32 + 4 x (shift, and-or).  The offset term is one
+//    more MFMA per chunk with A = (z, ..., z).  Bound: vector ALU.
+//  VER 2 (one scaling group per 128-column block): the four lanes that hold the four blocks of
+//    one row exchange dwords (4 x 4 transpose, v_permlane16_swap / v_permlane32_swap), after
+//    which lane (h, r) holds, for EVERY block B of row r, the chunks 4h..4h+3, and one MFMA step
+//    contracts 32 columns of a single block.  A is then just +-1.0, independent of the row: it
+//    comes from a 256-entry table in LDS (one ds_read_b128 per 8 signs; 8 interleaved copies so
+//    that neighbouring lanes read different banks); LDS_STEPS of the 4 steps of a block use the
+//    table, the others expand in registers.  The products of one block are collected in a
+//    temporary accumulator and scaled by alpha (fp32) when the block is done; the scales are
+//    fetched into the accumulator's row layout with ds_bpermute.  The offset term uses A = all
+//    ones: the block's column sums of X, scaled by z.  Bound: LDS read bandwidth.
+//  In both, the pairing inside an octet (elements 2d, 2d+1 <-> columns d, d+4) is arbitrary as
+//  long as A and B agree; X is stored in LDS in that order.
 #include "bcq_internal.h"
 #include "bcq_device.h"
 
@@ -36,7 +50,8 @@ struct SkinnyParams {
     uint16_t *Y;
     unsigned long long *accum;  // [batch][Mp]
     int M, N, Mp, batch, ldx, ldy;
-    int ntile, nslice, ntg, parts;  // ntg = ceil(ntile / 4) tile groups
+    int ntile, nslice, ntg;  // ntg = ceil(ntile / 4) tile groups (the four row tiles of a workgroup)
+    int units;               // ntg * nslice work units; workgroup w owns units [w*units/G, (w+1)*units/G)
     unsigned tile_bytes;
 };
 
@@ -164,13 +179,14 @@ __device__ __forceinline__ uint32_t scale_bits(const TileRegs<Q, Z, SUB> &t, int
 // 32 x 16 block is first turned through LDS (`stage`, private to the wave, kStageFloats floats) so
 // that lanes 0..31 and 32..63 each hold 32 consecutive rows of one batch column: a store or atomic
 // instruction then covers whole 64-byte lines of Y / of the accumulator words instead of
-// scattered 8-byte pieces.  With one K part the values are stored directly; otherwise the parts
-// are combined with the fixed-point split-K atomics (see bcq_device.h).
+// scattered 8-byte pieces.  `arrivals` = number of workgroups that contribute to this tile group:
+// with one the values are stored directly; otherwise they are combined with the fixed-point
+// split-K atomics (see bcq_device.h).
 constexpr int kStagePitch = 33;
-constexpr int kStageFloats = 17 * kStagePitch;
+constexpr int kStageFloats = 17 * kStagePitch + 15;  // 576
 
 __device__ __forceinline__ void skinny_store(const SkinnyParams &p, const f32x4 (&acc)[2], int tile, int lane,
-                                             float *stage)
+                                             float *stage, int arrivals)
 {
     const int r = lane & 15, h = lane >> 4;
 #pragma unroll
@@ -182,7 +198,7 @@ __device__ __forceinline__ void skinny_store(const SkinnyParams &p, const f32x4 
     float v[8];
 #pragma unroll
     for (int k = 0; k < 8; ++k) v[k] = stage[(2 * k + half) * kStagePitch + (lane & 31)];
-    if (p.parts == 1) {
+    if (arrivals == 1) {
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
             const int col = 2 * k + half;
@@ -190,192 +206,129 @@ __device__ __forceinline__ void skinny_store(const SkinnyParams &p, const f32x4 
         }
         return;
     }
-    unsigned long long mine[8], old[8];
+    // two rounds of four instructions: enough atomics in flight, fewer registers
 #pragma unroll
-    for (int k = 0; k < 8; ++k) {
-        const int col = 2 * k + half;
-        mine[k] = encode_partial(v[k]);
-        old[k] = 0;
-        if (col < p.batch)
-            old[k] = __hip_atomic_fetch_add(p.accum + (size_t)col * p.Mp + row, mine[k], __ATOMIC_RELAXED,
-                                            __HIP_MEMORY_SCOPE_AGENT);
-    }
+    for (int k0 = 0; k0 < 8; k0 += 4) {
+        unsigned long long mine[4], old[4];
 #pragma unroll
-    for (int k = 0; k < 8; ++k) {
-        const int col = 2 * k + half;
-        const unsigned long long total = old[k] + mine[k];
-        if (col < p.batch && arrivals_of(total) == (unsigned)p.parts) {
-            if (row < p.M) p.Y[(size_t)col * p.ldy + row] = float_to_half_bits(decode_total(total));
-            __hip_atomic_store(p.accum + (size_t)col * p.Mp + row, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        for (int k = 0; k < 4; ++k) {
+            const int col = 2 * (k0 + k) + half;
+            mine[k] = encode_partial(v[k0 + k]);
+            old[k] = 0;
+            if (col < p.batch)
+                old[k] = __hip_atomic_fetch_add(p.accum + (size_t)col * p.Mp + row, mine[k], __ATOMIC_RELAXED,
+                                                __HIP_MEMORY_SCOPE_AGENT);
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int col = 2 * (k0 + k) + half;
+            const unsigned long long total = old[k] + mine[k];
+            if (col < p.batch && arrivals_of(total) == (unsigned)arrivals) {
+                if (row < p.M) p.Y[(size_t)col * p.ldy + row] = float_to_half_bits(decode_total(total));
+                __hip_atomic_store(p.accum + (size_t)col * p.Mp + row, 0ull, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+            }
         }
     }
 }
 
-template <int Q, int Z, int SUB>
-__global__ __launch_bounds__(256) void bcq_skinny_kernel(SkinnyParams p)
+// First unit of workgroup w, and the workgroup that owns unit u, for `units` units cut into `groups`
+// contiguous ranges of floor/ceil(units / groups).
+__device__ __forceinline__ int first_unit(int w, int units, int groups)
 {
-    __shared__ __attribute__((aligned(16))) uint8_t xs[2 * kXBufBytes];
+    return (int)(((long long)w * units) / groups);
+}
 
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: tile pointers stay in SGPRs
-    const int tg = blockIdx.x % p.ntg, part = blockIdx.x / p.ntg;
-    const int tile = 4 * tg + wave;
-    const bool active = tile < p.ntile;
-    const int s_begin = (int)(((long long)part * p.nslice) / p.parts);
-    const int s_end = (int)(((long long)(part + 1) * p.nslice) / p.parts);
-    const int r = lane & 15, h = lane >> 4;
-    const size_t slice_stride = (size_t)p.ntile * p.tile_bytes;
-    const uint8_t *tile_ptr = p.blob + ((size_t)s_begin * p.ntile + (active ? tile : 0)) * p.tile_bytes;
+__device__ __forceinline__ int owner_of_unit(int u, int units, int groups)
+{
+    return (int)((((long long)u + 1) * groups - 1) / units);
+}
 
-    const __amdgpu_buffer_rsrc_t xrsrc = x_descriptor(p);
-    TileRegs<Q, Z, SUB> cur;
-    load_tile_buf<Q, Z, SUB>(cur, tile_descriptor(tile_ptr, p.tile_bytes, active && s_begin < s_end), lane);
-    {
-        u32x4 xr[4];
-        x_slice_load(p, xrsrc, s_begin, true, tid, xr);
-        x_slice_store(xs, tid, xr);
+// ---------------------------------------------------------------------------------
+// VER 1: one tile and slice, alpha folded into A
+// ---------------------------------------------------------------------------------
+template <int Q, int Z, int SUB>
+__device__ __forceinline__ void compute_folded(TileRegs<Q, Z, SUB> &cur, const uint8_t *xs_buf, int r, int h,
+                                               f32x4 (&acc)[2])
+{
+    // per (row half, plane): un-rotate, fold the sign of alpha into the bits, |alpha| pair
+    uint32_t abs_pair[2][Q][SUB];
+    uint32_t z_pair[2][SUB];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+#pragma unroll
+        for (int i = 0; i < Q; ++i) {
+            u32x4 w = cur.planes[t][i];
+            unrotate<SUB>(w, r);
+            uint32_t flip[SUB];
+#pragma unroll
+            for (int g = 0; g < SUB; ++g) {
+                const uint32_t ab = scale_bits<Q, Z, SUB>(cur, t, g, r, i);
+                flip[g] = (ab & 0x8000u) ? 0u : 0xffffffffu;  // bit 1 <-> +1
+                const uint32_t mag = ab & 0x7fffu;
+                abs_pair[t][i][g] = mag | (mag << 16);
+            }
+            // dword d of the un-permuted value belongs to sub-group d * SUB / 4
+            w.x ^= flip[0];
+            w.y ^= flip[SUB == 4 ? 1 : 0];
+            w.z ^= flip[SUB == 4 ? 2 : SUB - 1];
+            w.w ^= flip[SUB - 1];
+            cur.planes[t][i] = w;
+        }
+        if (Z) {
+#pragma unroll
+            for (int g = 0; g < SUB; ++g) {
+                const uint32_t zb = scale_bits<Q, Z, SUB>(cur, t, g, r, Q);
+                z_pair[t][g] = zb | (zb << 16);
+            }
+        }
     }
-    __syncthreads();
-
-    f32x4 acc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
-
-    for (int slice = s_begin; slice < s_end; ++slice) {
-        const bool more = slice + 1 < s_end;
-        TileRegs<Q, Z, SUB> nxt;
-        u32x4 xr[4];
-        tile_ptr += slice_stride;
-        // unconditional requests for the next slice (empty descriptor / out-of-range offsets when
-        // there is none): they stay in flight while this slice is computed
-        load_tile_buf<Q, Z, SUB>(nxt, tile_descriptor(tile_ptr, p.tile_bytes, more && active), lane);
-        x_slice_load(p, xrsrc, slice + 1, more, tid, xr);
-        if (active) {
-            // per (row half, plane): un-rotate, fold the sign of alpha into the bits, |alpha| pair
-            uint32_t abs_pair[2][Q][SUB];
-            uint32_t z_pair[2][SUB];
+    const uint8_t *xb = xs_buf + r * kXPitchBytes + h * 256;
+#pragma unroll
+    for (int dq = 0; dq < 4; ++dq) {
+        constexpr int per = 4 / SUB;  // dwords (of 4 chunks) per scaling sub-group
+        const int g = dq / per;
+        uint32_t w[2][Q], w4[2][Q];
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int i = 0; i < Q; ++i) {
+                w[t][i] = cur.planes[t][i][dq];
+                w4[t][i] = w[t][i] >> 4;
+            }
+#pragma unroll
+        for (int n = 0; n < 4; ++n) {
+            const f16x8 bx = *reinterpret_cast<const f16x8 *>(xb + (4 * dq + n) * 16);
 #pragma unroll
             for (int t = 0; t < 2; ++t) {
 #pragma unroll
                 for (int i = 0; i < Q; ++i) {
-                    u32x4 w = cur.planes[t][i];
-                    unrotate<SUB>(w, r);
-                    uint32_t flip[SUB];
-#pragma unroll
-                    for (int g = 0; g < SUB; ++g) {
-                        const uint32_t ab = scale_bits<Q, Z, SUB>(cur, t, g, r, i);
-                        flip[g] = (ab & 0x8000u) ? 0u : 0xffffffffu;  // bit 1 <-> +1
-                        const uint32_t mag = ab & 0x7fffu;
-                        abs_pair[t][i][g] = mag | (mag << 16);
-                    }
-                    // dword d of the un-permuted value belongs to sub-group d * SUB / 4
-                    w.x ^= flip[0];
-                    w.y ^= flip[SUB == 4 ? 1 : 0];
-                    w.z ^= flip[SUB == 4 ? 2 : SUB - 1];
-                    w.w ^= flip[SUB - 1];
-                    cur.planes[t][i] = w;
+                    f16x8 a;
+                    if (n == 0) a = expand_byte<0>(w[t][i], w4[t][i], abs_pair[t][i][g]);
+                    if (n == 1) a = expand_byte<1>(w[t][i], w4[t][i], abs_pair[t][i][g]);
+                    if (n == 2) a = expand_byte<2>(w[t][i], w4[t][i], abs_pair[t][i][g]);
+                    if (n == 3) a = expand_byte<3>(w[t][i], w4[t][i], abs_pair[t][i][g]);
+                    acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, bx, acc[t], 0, 0, 0);
                 }
                 if (Z) {
-#pragma unroll
-                    for (int g = 0; g < SUB; ++g) {
-                        const uint32_t zb = scale_bits<Q, Z, SUB>(cur, t, g, r, Q);
-                        z_pair[t][g] = zb | (zb << 16);
-                    }
-                }
-            }
-            const uint8_t *xb = xs + (slice - s_begin & 1) * kXBufBytes + r * kXPitchBytes + h * 256;
-#pragma unroll
-            for (int dq = 0; dq < 4; ++dq) {
-                constexpr int per = 4 / SUB;  // dwords (of 4 chunks) per scaling sub-group
-                const int g = dq / per;
-                uint32_t w[2][Q], w4[2][Q];
-#pragma unroll
-                for (int t = 0; t < 2; ++t)
-#pragma unroll
-                    for (int i = 0; i < Q; ++i) {
-                        w[t][i] = cur.planes[t][i][dq];
-                        w4[t][i] = w[t][i] >> 4;
-                    }
-#pragma unroll
-                for (int n = 0; n < 4; ++n) {
-                    const f16x8 bx = *reinterpret_cast<const f16x8 *>(xb + (4 * dq + n) * 16);
-#pragma unroll
-                    for (int t = 0; t < 2; ++t) {
-#pragma unroll
-                        for (int i = 0; i < Q; ++i) {
-                            f16x8 a;
-                            if (n == 0) a = expand_byte<0>(w[t][i], w4[t][i], abs_pair[t][i][g]);
-                            if (n == 1) a = expand_byte<1>(w[t][i], w4[t][i], abs_pair[t][i][g]);
-                            if (n == 2) a = expand_byte<2>(w[t][i], w4[t][i], abs_pair[t][i][g]);
-                            if (n == 3) a = expand_byte<3>(w[t][i], w4[t][i], abs_pair[t][i][g]);
-                            acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, bx, acc[t], 0, 0, 0);
-                        }
-                        if (Z) {
-                            const u32x4 zz = {z_pair[t][g], z_pair[t][g], z_pair[t][g], z_pair[t][g]};
-                            acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, zz), bx, acc[t],
-                                                                            0, 0, 0);
-                        }
-                    }
+                    const u32x4 zz = {z_pair[t][g], z_pair[t][g], z_pair[t][g], z_pair[t][g]};
+                    acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, zz), bx, acc[t], 0, 0, 0);
                 }
             }
         }
-        if (more) {
-            x_slice_store(xs + (slice + 1 - s_begin & 1) * kXBufBytes, tid, xr);
-            if (active) cur = nxt;
-        }
-        __syncthreads();  // next X slice written, everyone done reading the current one
     }
-
-    if (!active) return;
-    // the X buffers are free after the loop's last barrier: each wave stages its block there
-    skinny_store(p, acc, tile, lane, reinterpret_cast<float *>(xs) + wave * kStageFloats);
 }
 
 // ---------------------------------------------------------------------------------
-// Second version of the kernel, for one scaling group per 128-column block (group a multiple
-// of 128, or the whole row).  The first version spends nearly all its time in the vector ALU
-// turning sign bits into +-alpha operands (9 operations per 8 signs).  Two changes cut that:
-//
-//  * The four lanes (h = 0..3) that hold the four blocks of one row exchange dwords (a 4 x 4
-//    transpose with v_permlane16_swap / v_permlane32_swap), after which lane (h, r) holds, for
-//    EVERY block B of row r, the chunks 4h..4h+3.  One MFMA step then contracts 32 columns of a
-//    single block, so alpha no longer has to be folded into A: A is just +-1.0, the products of
-//    one block are collected in a temporary accumulator and scaled by alpha (fp32) when the
-//    block is done.  The scales are fetched into the accumulator's row layout with ds_bpermute.
-//  * +-1.0 operands do not depend on the row, so most of them come from a 256-entry table in
-//    LDS (one ds_read_b128 per 8 signs, 8 interleaved copies so that any 8 neighbouring lanes
-//    read different banks); the rest are still expanded in registers, which keeps the LDS pipe
-//    and the vector ALU about equally busy.  LDS_STEPS of the 4 MFMA steps of a block use the table.
-//
-// The offset term uses A = all ones: the block's column sums of X, scaled by z afterwards.
+// VER 2: lane transpose, +-1.0 operands from the LDS table, alpha applied to the accumulators
+// ---------------------------------------------------------------------------------
 constexpr int kTabCopies = 8;
 constexpr int kTabBytes = 256 * kTabCopies * 16;  // 32 KB
 
-template <int Q, int Z, int LDS_STEPS>
-__global__ __launch_bounds__(256) void bcq_skinny2_kernel(SkinnyParams p)
+// Sign table: entry b holds 8 binary16 values, pair d = (bit d, bit d + 4) of b, +1.0 for a set bit
+// (the element order the staged X uses); copy c of entry b sits at (8 b + c) * 16.
+__device__ __forceinline__ void build_sign_table(uint8_t *tab, int tid)
 {
-    __shared__ __attribute__((aligned(16))) uint8_t xs[2 * kXBufBytes];
-    __shared__ __attribute__((aligned(16))) uint8_t tab[kTabBytes];
-
-    const int tid = threadIdx.x, lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: tile pointers stay in SGPRs
-    const int tg = blockIdx.x % p.ntg, part = blockIdx.x / p.ntg;
-    const int tile = 4 * tg + wave;
-    const bool active = tile < p.ntile;
-    const int s_begin = (int)(((long long)part * p.nslice) / p.parts);
-    const int s_end = (int)(((long long)(part + 1) * p.nslice) / p.parts);
-    const int r = lane & 15, h = lane >> 4;
-    const size_t slice_stride = (size_t)p.ntile * p.tile_bytes;
-    const uint8_t *tile_ptr = p.blob + ((size_t)s_begin * p.ntile + (active ? tile : 0)) * p.tile_bytes;
-
-    const __amdgpu_buffer_rsrc_t xrsrc = x_descriptor(p);
-    TileRegs<Q, Z, 1> cur;
-    load_tile_buf<Q, Z, 1>(cur, tile_descriptor(tile_ptr, p.tile_bytes, active && s_begin < s_end), lane);
-    {
-        u32x4 xr[4];
-        x_slice_load(p, xrsrc, s_begin, true, tid, xr);
-        x_slice_store(xs, tid, xr);
-    }
-    // Sign table: entry b holds 8 binary16 values, pair d = (bit d, bit d + 4) of b, +1.0 for a set
-    // bit (the element order the staged X uses); copy c of entry b sits at (8 b + c) * 16.
 #pragma unroll
     for (int k = 0; k < 8; ++k) {
         const int idx = tid + 256 * k, b = idx >> 3;
@@ -385,182 +338,243 @@ __global__ __launch_bounds__(256) void bcq_skinny2_kernel(SkinnyParams p)
             e[d] = (((b >> d) & 1) ? 0x3c00u : 0xbc00u) | ((((b >> (d + 4)) & 1) ? 0x3c00u : 0xbc00u) << 16);
         *reinterpret_cast<u32x4 *>(tab + idx * 16) = e;
     }
-    __syncthreads();
-    const uint8_t *my_tab = tab + (lane & (kTabCopies - 1)) * 16;
+}
 
-    f32x4 acc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+template <int Q, int Z, int LDS_STEPS>
+__device__ __forceinline__ void compute_table(const TileRegs<Q, Z, 1> &cur, const uint8_t *xs_buf, const uint8_t *my_tab,
+                                              int r, int h, f32x4 (&acc)[2])
+{
+    // chunk order, then the 4 x 4 dword transpose across the lanes r, r+16, r+32, r+48:
+    // wb[t][i][B] = chunks 4h .. 4h+3 of (row 16t + r, block B, plane i)
+    uint32_t wb[2][Q][4];
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int i = 0; i < Q; ++i) {
+            u32x4 w = cur.planes[t][i];
+            unrotate<1>(w, r);
+            const auto e01 = __builtin_amdgcn_permlane16_swap(w.x, w.y, false, false);
+            const auto e23 = __builtin_amdgcn_permlane16_swap(w.z, w.w, false, false);
+            const auto f02 = __builtin_amdgcn_permlane32_swap(e01[0], e23[0], false, false);
+            const auto f13 = __builtin_amdgcn_permlane32_swap(e01[1], e23[1], false, false);
+            wb[t][i][0] = f02[0]; wb[t][i][1] = f13[0]; wb[t][i][2] = f02[1]; wb[t][i][3] = f13[1];
+        }
+    const uint8_t *xb = xs_buf + r * kXPitchBytes + h * 64;
     const u32x4 ones = {0x3c003c00u, 0x3c003c00u, 0x3c003c00u, 0x3c003c00u};
-
-    for (int slice = s_begin; slice < s_end; ++slice) {
-        const bool more = slice + 1 < s_end;
-        TileRegs<Q, Z, 1> nxt;
-        u32x4 xr[4];
-        tile_ptr += slice_stride;
-        // unconditional requests for the next slice (empty descriptor / out-of-range offsets when
-        // there is none): they stay in flight while this slice is computed
-        load_tile_buf<Q, Z, 1>(nxt, tile_descriptor(tile_ptr, p.tile_bytes, more && active), lane);
-        x_slice_load(p, xrsrc, slice + 1, more, tid, xr);
-        if (active) {
-            // chunk order, then the 4 x 4 dword transpose across the lanes r, r+16, r+32, r+48:
-            // wb[t][i][B] = chunks 4h .. 4h+3 of (row 16t + r, block B, plane i)
-            uint32_t wb[2][Q][4];
+#pragma unroll
+    for (int B = 0; B < 4; ++B) {
+        // scales of rows 4h + j of this block, held by lanes 16 B + 4h + j, into this lane
+        uint32_t sc[4][Q + Z];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int e = 0; e < Q + Z; ++e)
+                sc[j][e] = (uint32_t)__builtin_amdgcn_ds_bpermute(4 * (16 * B + 4 * h + j), (int)cur.scales[e]);
+        f32x4 C[2][Q];
+        f32x4 Cz = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int i = 0; i < Q; ++i) C[t][i] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const f16x8 bx = *reinterpret_cast<const f16x8 *>(xb + (16 * B + s) * 16);
 #pragma unroll
             for (int t = 0; t < 2; ++t)
 #pragma unroll
                 for (int i = 0; i < Q; ++i) {
-                    u32x4 w = cur.planes[t][i];
-                    unrotate<1>(w, r);
-                    const auto e01 = __builtin_amdgcn_permlane16_swap(w.x, w.y, false, false);
-                    const auto e23 = __builtin_amdgcn_permlane16_swap(w.z, w.w, false, false);
-                    const auto f02 = __builtin_amdgcn_permlane32_swap(e01[0], e23[0], false, false);
-                    const auto f13 = __builtin_amdgcn_permlane32_swap(e01[1], e23[1], false, false);
-                    wb[t][i][0] = f02[0]; wb[t][i][1] = f13[0]; wb[t][i][2] = f02[1]; wb[t][i][3] = f13[1];
-                }
-            const uint8_t *xb = xs + (slice - s_begin & 1) * kXBufBytes + r * kXPitchBytes + h * 64;
-            // The 16 MFMA steps (block B = step / 4, chunk group s = step % 4) are software-pipelined:
-            // the operands of step k+1 are requested from LDS before the MFMAs of step k are issued.
-            auto fetch = [&](int step, f16x8 (&a)[2][Q], f16x8 &bx) {
-                const int B = step >> 2, s = step & 3;
-                bx = *reinterpret_cast<const f16x8 *>(xb + (16 * B + s) * 16);
-#pragma unroll
-                for (int t = 0; t < 2; ++t)
-#pragma unroll
-                    for (int i = 0; i < Q; ++i) {
-                        const uint32_t w = wb[t][i][B];
-                        if (s < LDS_STEPS) {
-                            const uint32_t byte = (w >> (8 * s)) & 0xffu;
-                            a[t][i] = *reinterpret_cast<const f16x8 *>(my_tab + byte * (16 * kTabCopies));
-                        } else {
-                            const uint32_t wn = ~w, wn4 = wn >> 4;
-                            if (s == 0) a[t][i] = expand_byte<0>(wn, wn4, 0x3c003c00u);
-                            if (s == 1) a[t][i] = expand_byte<1>(wn, wn4, 0x3c003c00u);
-                            if (s == 2) a[t][i] = expand_byte<2>(wn, wn4, 0x3c003c00u);
-                            if (s == 3) a[t][i] = expand_byte<3>(wn, wn4, 0x3c003c00u);
-                        }
+                    const uint32_t w = wb[t][i][B];
+                    f16x8 a;
+                    if (s < LDS_STEPS) {
+                        const uint32_t byte = (w >> (8 * s)) & 0xffu;
+                        a = *reinterpret_cast<const f16x8 *>(my_tab + byte * (16 * kTabCopies));
+                    } else {
+                        const uint32_t wn = ~w, wn4 = wn >> 4;
+                        if (s == 0) a = expand_byte<0>(wn, wn4, 0x3c003c00u);
+                        if (s == 1) a = expand_byte<1>(wn, wn4, 0x3c003c00u);
+                        if (s == 2) a = expand_byte<2>(wn, wn4, 0x3c003c00u);
+                        if (s == 3) a = expand_byte<3>(wn, wn4, 0x3c003c00u);
                     }
-            };
-            f16x8 abuf[2][2][Q], bbuf[2];
-            fetch(0, abuf[0], bbuf[0]);
-            f32x4 C[2][Q];
-            f32x4 Cz = {0.f, 0.f, 0.f, 0.f};
-            uint32_t sc[4][Q + Z];
-#pragma unroll
-            for (int step = 0; step < 16; ++step) {
-                const int B = step >> 2, s = step & 3, cb = step & 1;
-                if (step + 1 < 16) fetch(step + 1, abuf[cb ^ 1], bbuf[cb ^ 1]);
-                if (s == 0) {
-                    // scales of rows 4h + j of this block, held by lanes 16 B + 4h + j, into this lane
-#pragma unroll
-                    for (int j = 0; j < 4; ++j)
-#pragma unroll
-                        for (int e = 0; e < Q + Z; ++e)
-                            sc[j][e] = (uint32_t)__builtin_amdgcn_ds_bpermute(4 * (16 * B + 4 * h + j), (int)cur.scales[e]);
-#pragma unroll
-                    for (int t = 0; t < 2; ++t)
-#pragma unroll
-                        for (int i = 0; i < Q; ++i) C[t][i] = f32x4{0.f, 0.f, 0.f, 0.f};
-                    Cz = f32x4{0.f, 0.f, 0.f, 0.f};
+                    C[t][i] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, bx, C[t][i], 0, 0, 0);
                 }
-                __builtin_amdgcn_sched_barrier(0);
+            if (Z) Cz = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, ones), bx, Cz, 0, 0, 0);
+        }
+        // acc[t][j] += alpha_i(row 16t + 4h + j, block B) * C[t][i][j]  (+ z * column sums)
 #pragma unroll
-                for (int t = 0; t < 2; ++t)
+        for (int t = 0; t < 2; ++t)
 #pragma unroll
-                    for (int i = 0; i < Q; ++i)
-                        C[t][i] = __builtin_amdgcn_mfma_f32_16x16x32_f16(abuf[cb][t][i], bbuf[cb], C[t][i], 0, 0, 0);
-                if (Z)
-                    Cz = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, ones), bbuf[cb], Cz, 0, 0, 0);
-                __builtin_amdgcn_sched_barrier(0);
-                if (s == 3) {
-                    // acc[t][j] += alpha_i(row 16t + 4h + j, block B) * C[t][i][j]  (+ z * column sums)
+            for (int j = 0; j < 4; ++j) {
 #pragma unroll
-                    for (int t = 0; t < 2; ++t)
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-#pragma unroll
-                            for (int c = 0; c < Q + Z; ++c) {
-                                const int e = t * (Q + Z) + c;  // half index in the lane's scale record
-                                const uint32_t pair = sc[j][e >> 1];
-                                const float v = half_bits_to_float((e & 1) ? (pair >> 16) : (pair & 0xffffu));
-                                acc[t][j] = fmaf(v, c < Q ? C[t][c < Q ? c : 0][j] : Cz[j], acc[t][j]);
-                            }
-                        }
+                for (int c = 0; c < Q + Z; ++c) {
+                    const int e = t * (Q + Z) + c;  // half index in the lane's scale record
+                    const uint32_t pair = sc[j][e >> 1];
+                    const float v = half_bits_to_float((e & 1) ? (pair >> 16) : (pair & 0xffffu));
+                    acc[t][j] = fmaf(v, c < Q ? C[t][c < Q ? c : 0][j] : Cz[j], acc[t][j]);
                 }
             }
-        }
-        if (more) {
-            x_slice_store(xs + (slice + 1 - s_begin & 1) * kXBufBytes, tid, xr);
-            if (active) cur = nxt;
-        }
-        __syncthreads();  // next X slice written, everyone done reading the current one
     }
+}
 
-    if (!active) return;
-    // the X buffers are free after the loop's last barrier: each wave stages its block there
-    skinny_store(p, acc, tile, lane, reinterpret_cast<float *>(xs) + wave * kStageFloats);
+// ---------------------------------------------------------------------------------
+// the kernel
+// ---------------------------------------------------------------------------------
+template <int Q, int Z, int SUB, int VER, int LDS_STEPS>
+__global__ __launch_bounds__(256) void bcq_skinny_kernel(SkinnyParams p)
+{
+    static_assert(VER == 1 || SUB == 1, "the table kernel needs one scaling group per block");
+    __shared__ __attribute__((aligned(16))) uint8_t xs[2 * kXBufBytes];
+    __shared__ __attribute__((aligned(16))) uint8_t tab[VER == 2 ? kTabBytes : 16];
+    __shared__ float stage[4 * kStageFloats];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: tile pointers stay in SGPRs
+    const int r = lane & 15, h = lane >> 4;
+    const int groups = gridDim.x;
+    const int u_begin = first_unit(blockIdx.x, p.units, groups), u_end = first_unit(blockIdx.x + 1, p.units, groups);
+    if (u_begin >= u_end) return;  // uniform for the workgroup, before any barrier
+
+    int tg = u_begin / p.nslice, slice = u_begin - tg * p.nslice;
+    int tile = 4 * tg + wave;
+    bool active = tile < p.ntile;
+
+    const __amdgpu_buffer_rsrc_t xrsrc = x_descriptor(p);
+    TileRegs<Q, Z, SUB> cur;
+    load_tile_buf<Q, Z, SUB>(
+        cur, tile_descriptor(p.blob + ((size_t)slice * p.ntile + (active ? tile : 0)) * p.tile_bytes, p.tile_bytes, active),
+        lane);
+    {
+        u32x4 xr[4];
+        x_slice_load(p, xrsrc, slice, true, tid, xr);
+        x_slice_store(xs, tid, xr);
+    }
+    if (VER == 2) build_sign_table(tab, tid);
+    __syncthreads();
+    const uint8_t *my_tab = tab + (lane & (kTabCopies - 1)) * 16;
+
+    int buf = 0;
+    int u = u_begin;
+    while (u < u_end) {
+        // one segment: the units of this workgroup that belong to tile group `tg`
+        const int seg_end = min(u_end, (tg + 1) * p.nslice);
+        const int seg_tg = tg, seg_tile = tile;
+        const bool seg_active = active;
+        f32x4 acc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+        for (; u < seg_end; ++u) {
+            // the next unit of this workgroup, if any (it may be the first of the next segment)
+            const bool more = u + 1 < u_end;
+            int n_slice = slice + 1, n_tg = tg;
+            if (n_slice == p.nslice) { n_slice = 0; n_tg = tg + 1; }
+            const int n_tile = 4 * n_tg + wave;
+            const bool n_active = more && n_tile < p.ntile;
+            // unconditional requests for it (empty descriptor / out-of-range offsets when there is
+            // none): they stay in flight while this unit is computed
+            TileRegs<Q, Z, SUB> nxt;
+            u32x4 xr[4];
+            load_tile_buf<Q, Z, SUB>(
+                nxt,
+                tile_descriptor(p.blob + ((size_t)n_slice * p.ntile + (n_active ? n_tile : 0)) * p.tile_bytes,
+                                p.tile_bytes, n_active),
+                lane);
+            x_slice_load(p, xrsrc, n_slice, more, tid, xr);
+
+            if (active) {
+                if constexpr (VER == 1) compute_folded<Q, Z, SUB>(cur, xs + buf * kXBufBytes, r, h, acc);
+                else compute_table<Q, Z, LDS_STEPS>(cur, xs + buf * kXBufBytes, my_tab, r, h, acc);
+            }
+            if (more) {
+                x_slice_store(xs + (buf ^ 1) * kXBufBytes, tid, xr);
+                cur = nxt;
+            }
+            tg = n_tg; slice = n_slice; tile = n_tile; active = n_active; buf ^= 1;
+            __syncthreads();  // next X slice written, everyone done reading the current one
+        }
+        // this workgroup is done with the tile group: flush (the next segment's first loads are in flight)
+        if (seg_active) {
+            const int arrivals = owner_of_unit((seg_tg + 1) * p.nslice - 1, p.units, groups) -
+                                 owner_of_unit(seg_tg * p.nslice, p.units, groups) + 1;
+            // (the lane index is passed through an empty asm so that the per-lane address arithmetic of
+            // the flush is not hoisted out of this loop into registers that stay live during the units)
+            int flush_lane = lane;
+            asm volatile("" : "+v"(flush_lane));
+            skinny_store(p, acc, seg_tile, flush_lane, stage + wave * kStageFloats, arrivals);
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------
-int auto_skinny_parts(const Geom &g)
+// Number of workgroups of a kernel the current device holds at once (asked once per kernel).
+template <int Q, int Z, int SUB, int VER, int LDS_STEPS>
+static int resident_groups()
 {
-    // about 2000 waves in flight (8 per CU), at least one slice per part
-    const int waves_per_part = ((g.ntile + 3) / 4) * 4;
-    int parts = (2048 + waves_per_part / 2) / waves_per_part;
-    if (parts < 1) parts = 1;
-    if (parts > g.nslice) parts = g.nslice;
-    return parts;
+    static int cached = 0;
+    if (cached == 0) {
+        int per_cu = 0, dev = 0, cus = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, bcq_skinny_kernel<Q, Z, SUB, VER, LDS_STEPS>, 256, 0) !=
+                hipSuccess || per_cu < 1)
+            per_cu = 1;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+            cus = 256;
+        cached = per_cu * cus;
+    }
+    return cached;
 }
 
-template <int Q, int Z, int SUB>
-static hipError_t launch_skinny_one(const SkinnyParams &p, hipStream_t stream)
+// Grid size: `parts` > 0: that many workgroups per tile group (a K split); `parts` < 0: -parts
+// workgroups; 0: as many workgroups as are resident.
+template <int Q, int Z, int SUB, int VER, int LDS_STEPS>
+static hipError_t launch_skinny_one(const SkinnyParams &p, int parts, bool single_slice, hipStream_t stream)
 {
-    hipLaunchKernelGGL((bcq_skinny_kernel<Q, Z, SUB>), dim3((unsigned)(p.ntg * p.parts)), dim3(256), 0, stream, p);
-    return hipGetLastError();
-}
-
-template <int Q, int Z, int LDS_STEPS>
-static hipError_t launch_skinny2_one(const SkinnyParams &p, hipStream_t stream)
-{
-    hipLaunchKernelGGL((bcq_skinny2_kernel<Q, Z, LDS_STEPS>), dim3((unsigned)(p.ntg * p.parts)), dim3(256), 0, stream,
-                       p);
+    long long groups = parts > 0 ? (long long)parts * p.ntg
+                                 : parts < 0 ? -(long long)parts : resident_groups<Q, Z, SUB, VER, LDS_STEPS>();
+    if (groups > p.units) groups = p.units;
+    if (single_slice) groups = p.ntg;  // no workspace: one unit per tile group, nothing to combine
+    if (groups < 1) groups = 1;
+    hipLaunchKernelGGL((bcq_skinny_kernel<Q, Z, SUB, VER, LDS_STEPS>), dim3((unsigned)groups), dim3(256), 0, stream, p);
     return hipGetLastError();
 }
 
 template <int Q, int Z>
-static hipError_t launch_skinny_qz(const SkinnyParams &p, int sub, int version, int lds_steps, hipStream_t stream)
+static hipError_t launch_skinny_qz(const SkinnyParams &p, int parts, bool single_slice, int sub, int version,
+                                   int lds_steps, hipStream_t stream)
 {
-    if (sub == 2) return launch_skinny_one<Q, Z, 2>(p, stream);
-    if (sub == 4) return launch_skinny_one<Q, Z, 4>(p, stream);
-    if (version == 1) return launch_skinny_one<Q, Z, 1>(p, stream);
+    if (sub == 2) return launch_skinny_one<Q, Z, 2, 1, 0>(p, parts, single_slice, stream);
+    if (sub == 4) return launch_skinny_one<Q, Z, 4, 1, 0>(p, parts, single_slice, stream);
+    if (version == 1) return launch_skinny_one<Q, Z, 1, 1, 0>(p, parts, single_slice, stream);
     // all four MFMA steps of a block from the LDS table measured fastest; 3 (one step expanded in
     // registers) is kept as the alternative for tuning runs
-    return lds_steps == 3 ? launch_skinny2_one<Q, Z, 3>(p, stream) : launch_skinny2_one<Q, Z, 4>(p, stream);
+    return lds_steps == 3 ? launch_skinny_one<Q, Z, 1, 2, 3>(p, parts, single_slice, stream)
+                          : launch_skinny_one<Q, Z, 1, 2, 4>(p, parts, single_slice, stream);
 }
 
 hipError_t launch_skinny(const Geom &g, const void *packed, const uint16_t *X, int ldx, uint16_t *Y, int ldy,
                          int batch, void *workspace, const GemvTuning &tuning, hipStream_t stream)
 {
-    const int parts = tuning.skinny_parts;
     SkinnyParams p;
     p.blob = static_cast<const uint8_t *>(packed);
     p.X = X; p.Y = Y;
     p.accum = static_cast<unsigned long long *>(workspace);
     p.M = g.M; p.N = g.N; p.Mp = g.Mp; p.batch = batch; p.ldx = ldx; p.ldy = ldy;
     p.ntile = g.ntile; p.nslice = g.nslice; p.ntg = (g.ntile + 3) / 4;
-    p.parts = parts > 0 ? parts : auto_skinny_parts(g);
-    if (p.parts > g.nslice) p.parts = g.nslice;
-    if (!workspace) p.parts = 1;  // only reachable for a single column slice
+    const long long units = (long long)p.ntg * g.nslice;
+    if (units > 0x7fffffffLL) return hipErrorInvalidValue;
+    p.units = (int)units;
     p.tile_bytes = g.tile_bytes;
+    // forced grid sizes (tuning runs, tests): a K split per tile group, or a plain number of workgroups
+    const int parts = tuning.skinny_parts > 0 ? tuning.skinny_parts : -tuning.workgroups;
+    const bool single = workspace == nullptr;  // only reachable for a single column slice
+    const int sub = g.sub, ver = tuning.skinny_version, steps = tuning.skinny_lds_steps;
     switch (g.q * 2 + g.z) {
-        case 2: return launch_skinny_qz<1, 0>(p, g.sub, tuning.skinny_version, tuning.skinny_lds_steps, stream);
-        case 3: return launch_skinny_qz<1, 1>(p, g.sub, tuning.skinny_version, tuning.skinny_lds_steps, stream);
-        case 4: return launch_skinny_qz<2, 0>(p, g.sub, tuning.skinny_version, tuning.skinny_lds_steps, stream);
-        case 5: return launch_skinny_qz<2, 1>(p, g.sub, tuning.skinny_version, tuning.skinny_lds_steps, stream);
-        case 6: return launch_skinny_qz<3, 0>(p, g.sub, tuning.skinny_version, tuning.skinny_lds_steps, stream);
-        case 7: return launch_skinny_qz<3, 1>(p, g.sub, tuning.skinny_version, tuning.skinny_lds_steps, stream);
-        case 8: return launch_skinny_qz<4, 0>(p, g.sub, tuning.skinny_version, tuning.skinny_lds_steps, stream);
-        case 9: return launch_skinny_qz<4, 1>(p, g.sub, tuning.skinny_version, tuning.skinny_lds_steps, stream);
+        case 2: return launch_skinny_qz<1, 0>(p, parts, single, sub, ver, steps, stream);
+        case 3: return launch_skinny_qz<1, 1>(p, parts, single, sub, ver, steps, stream);
+        case 4: return launch_skinny_qz<2, 0>(p, parts, single, sub, ver, steps, stream);
+        case 5: return launch_skinny_qz<2, 1>(p, parts, single, sub, ver, steps, stream);
+        case 6: return launch_skinny_qz<3, 0>(p, parts, single, sub, ver, steps, stream);
+        case 7: return launch_skinny_qz<3, 1>(p, parts, single, sub, ver, steps, stream);
+        case 8: return launch_skinny_qz<4, 0>(p, parts, single, sub, ver, steps, stream);
+        case 9: return launch_skinny_qz<4, 1>(p, parts, single, sub, ver, steps, stream);
     }
     return hipErrorInvalidValue;
 }

@@ -245,3 +245,24 @@ def test_skinny_kernel_variants(option, value, q, offset):
         assert np.array_equal(U.gpu_gemm(pl, U.x_dev(L)).astype(np.float64), expect)
     finally:
         bcq.set_option(option, 0)
+
+
+@pytest.mark.parametrize("workgroups", [1, 4, 7, 11, 29])
+@pytest.mark.parametrize("version", [1, 2])
+def test_skinny_work_split_does_not_change_results(workgroups, version):
+    """The skinny kernel cuts its (tile group, column slice) units into equal contiguous ranges, one
+    per workgroup; a range may end inside a tile group and continue in the next.  Any number of
+    workgroups gives the same bits on exact inputs (10 row tiles = 3 tile groups, the last one
+    partly empty; 10 column slices)."""
+    L = bcq_synth.make_exact_layer(300, 5120, 3, group=128, offset=True, batch=6, seed=31)
+    pl = U.upload_and_pack(L, max_batch=6)
+    expect = ref.gemm(L.planes, L.alpha, L.offset, L.x).astype(np.float16).astype(np.float64)
+    try:
+        bcq.set_option("skinny_version", version)
+        bcq.set_option("workgroups", workgroups)
+        Y = U.gpu_gemm(pl, U.x_dev(L)).astype(np.float64)
+    finally:
+        bcq.set_option("workgroups", 0)
+        bcq.set_option("skinny_version", 0)
+    assert np.array_equal(Y, expect)
+    assert not pl.workspace.cpu().numpy().any()
