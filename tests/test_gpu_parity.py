@@ -266,3 +266,36 @@ def test_skinny_work_split_does_not_change_results(workgroups, version):
         bcq.set_option("skinny_version", 0)
     assert np.array_equal(Y, expect)
     assert not pl.workspace.cpu().numpy().any()
+
+
+def test_graph_replay_matches_eager():
+    """The entry points only enqueue kernels (the workspace fill is a kernel, not a memset node), so
+    a captured sequence -- workspace init, GEMV, skinny GEMM -- can be replayed: every replay, with
+    eager calls and synchronisations in between, reproduces the eager results bit for bit."""
+    L = bcq_synth.make_layer(260, 2560, 3, group=128, offset=True, batch=5, seed=61)
+    pl = U.upload_and_pack(L, max_batch=5)
+    X = U.x_dev(L)
+    y_eager = pl.gemv(X[0]).clone()
+    Y_eager = pl.gemm_skinny(X).clone()
+    torch.cuda.synchronize()
+    y_g = torch.zeros_like(y_eager)
+    Y_g = torch.zeros_like(Y_eager)
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=stream):
+            bcq.workspace_init(pl.workspace)
+            pl.gemv(X[0], y_g)
+            pl.gemm_skinny(X, Y_g)
+    for rep in range(4):
+        y_g.fill_(7.0)
+        Y_g.fill_(7.0)
+        torch.cuda.synchronize()
+        with torch.cuda.stream(stream):
+            g.replay()
+        stream.synchronize()
+        assert torch.equal(y_g, y_eager), rep
+        assert torch.equal(Y_g, Y_eager), rep
+        # eager work of the program between replays
+        assert torch.equal(pl.gemm_skinny(X), Y_eager)
+        torch.cuda.synchronize()
