@@ -46,7 +46,7 @@ typedef enum {
 #define BCQ_LAYOUT_VERSION 1
 
 /* Largest batch bcq_gemm_skinny accepts. */
-#define BCQ_MAX_BATCH 16
+#define BCQ_MAX_BATCH 64
 
 /*
  * Problem descriptor (HOST, plain data, filled by the caller).
@@ -160,7 +160,9 @@ bcq_status bcq_gemv(const bcq_desc *desc, const void *packed, const uint16_t *x,
                     uint16_t *y, void *workspace, void *stream);
 
 /*
- * Y[j][m] = sum_k W_q[m][k] X[j][k],  1 <= batch <= BCQ_MAX_BATCH.
+ * Y[j][m] = sum_k W_q[m][k] X[j][k],  1 <= batch <= BCQ_MAX_BATCH.  The weights are read once
+ * per call for batch <= 64 with groups that are multiples of 128 (q <= 3; q = 4: once per 32
+ * columns), and once per 16 batch columns for groups of 32/64.
  *   X   DEVICE, row j starts at X + j*ldx (elements), ldx >= N, ldx % 8 == 0
  *   Y   DEVICE, row j starts at Y + j*ldy (elements), ldy >= M
  *   workspace as for bcq_gemv with bcq_workspace_bytes(desc, batch)

@@ -10,7 +10,7 @@ LIB_PATH = os.path.join(HERE, "libbcq.so")
 
 BCQ_OK, BCQ_ERR_INVALID_ARG, BCQ_ERR_UNSUPPORTED, BCQ_ERR_WORKSPACE, BCQ_ERR_HIP = range(5)
 BCQ_LAYOUT_VERSION = 1
-BCQ_MAX_BATCH = 16
+BCQ_MAX_BATCH = 64
 
 EXPORTS = ["bcq_packed_bytes", "bcq_workspace_bytes", "bcq_workspace_init", "bcq_pack",
            "bcq_pack_rows", "bcq_from_linear", "bcq_unpack", "bcq_gemv", "bcq_gemm_skinny", "bcq_read_probe_sink_bytes",

@@ -1,11 +1,12 @@
-// Skinny binary-coding GEMM for gfx950: Y[j][m] = sum_k W_q[m][k] X[j][k] for 2 <= batch <= 16
+// Skinny binary-coding GEMM for gfx950: Y[j][m] = sum_k W_q[m][k] X[j][k] for 2 <= batch <= 64
 // (paper Eq. 11 applied to a few activation vectors at once), reading the packed weights ONCE.
 //
 // With several activation vectors the work per weight bit grows with the batch while the
 // bytes do not, so the path stops being HBM-bound and the sign-sum tables of the batch-1
 // kernel (one table set per activation vector) no longer fit in LDS.  Here every sign becomes
 // a binary16 operand of the matrix cores (v_mfma_f32_16x16x32_f16, fp32 accumulate); the cost
-// is the same for every batch up to 16.
+// is the same for every batch up to 16; wider batches (up to 64, table kernel) reuse the expanded
+// operands for every group of 16 columns.
 //
 // Common skeleton (bcq_skinny_kernel<Q, Z, SUB, VER, LDS_STEPS>):
 //  * Same packed blob as the GEMV (bcq_layout.h).  A work unit is (tile group, column slice): the
@@ -61,15 +62,16 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 constexpr int kXPitchBytes = 1040;  // 64 chunks x 16 B + 16 B: batch rows land in different banks
 constexpr int kXBufBytes = 16 * kXPitchBytes;
 
-// Loads (into registers) this thread's share of the X slice: 4 chunks of 8 activations.  X is read
+// Loads (into registers) this thread's share of the X slice (16 NB batch rows): 4 NB chunks of 8 activations.  X is read
 // through a buffer descriptor covering its batch rows; chunks that do not exist (batch column or
 // column out of range, or no such slice: `wanted` false) are given an out-of-range offset and
 // come back as zeros, so the loads are unconditional.
+template <int NB>
 __device__ __forceinline__ void x_slice_load(const SkinnyParams &p, __amdgpu_buffer_rsrc_t xrsrc, int slice, bool wanted,
-                                             int tid, u32x4 (&xr)[4])
+                                             int tid, u32x4 (&xr)[4 * NB])
 {
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
+    for (int k = 0; k < 4 * NB; ++k) {
         const int idx = tid + 256 * k, chunk = idx & 63, c = idx >> 6;
         const int col = slice * kTileCols + kChunkCols * chunk;
         const bool ok = wanted && c < p.batch && col < p.N;
@@ -92,10 +94,11 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t tile_descriptor(const uint8_t 
 }
 
 // Stores them to LDS, elements reordered to (0,4,1,5,2,6,3,7) within a chunk.
-__device__ __forceinline__ void x_slice_store(uint8_t *xs, int tid, const u32x4 (&xr)[4])
+template <int NB>
+__device__ __forceinline__ void x_slice_store(uint8_t *xs, int tid, const u32x4 (&xr)[4 * NB])
 {
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
+    for (int k = 0; k < 4 * NB; ++k) {
         const int idx = tid + 256 * k, chunk = idx & 63, c = idx >> 6;
         const u32x4 v = xr[k];
         u32x4 o;
@@ -179,14 +182,14 @@ __device__ __forceinline__ uint32_t scale_bits(const TileRegs<Q, Z, SUB> &t, int
 // 32 x 16 block is first turned through LDS (`stage`, private to the wave, kStageFloats floats) so
 // that lanes 0..31 and 32..63 each hold 32 consecutive rows of one batch column: a store or atomic
 // instruction then covers whole 64-byte lines of Y / of the accumulator words instead of
-// scattered 8-byte pieces.  `arrivals` = number of workgroups that contribute to this tile group:
+// scattered 8-byte pieces.  `col0` = first batch column of the block; `arrivals` = number of workgroups that contribute to this tile group:
 // with one the values are stored directly; otherwise they are combined with the fixed-point
 // split-K atomics (see bcq_device.h).
 constexpr int kStagePitch = 33;
 constexpr int kStageFloats = 17 * kStagePitch + 15;  // 576
 
 __device__ __forceinline__ void skinny_store(const SkinnyParams &p, const f32x4 (&acc)[2], int tile, int lane,
-                                             float *stage, int arrivals)
+                                             float *stage, int arrivals, int col0)
 {
     const int r = lane & 15, h = lane >> 4;
 #pragma unroll
@@ -201,7 +204,7 @@ __device__ __forceinline__ void skinny_store(const SkinnyParams &p, const f32x4 
     if (arrivals == 1) {
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
-            const int col = 2 * k + half;
+            const int col = col0 + 2 * k + half;
             if (col < p.batch && row < p.M) p.Y[(size_t)col * p.ldy + row] = float_to_half_bits(v[k]);
         }
         return;
@@ -212,7 +215,7 @@ __device__ __forceinline__ void skinny_store(const SkinnyParams &p, const f32x4 
         unsigned long long mine[4], old[4];
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-            const int col = 2 * (k0 + k) + half;
+            const int col = col0 + 2 * (k0 + k) + half;
             mine[k] = encode_partial(v[k0 + k]);
             old[k] = 0;
             if (col < p.batch)
@@ -221,7 +224,7 @@ __device__ __forceinline__ void skinny_store(const SkinnyParams &p, const f32x4 
         }
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-            const int col = 2 * (k0 + k) + half;
+            const int col = col0 + 2 * (k0 + k) + half;
             const unsigned long long total = old[k] + mine[k];
             if (col < p.batch && arrivals_of(total) == (unsigned)arrivals) {
                 if (row < p.M) p.Y[(size_t)col * p.ldy + row] = float_to_half_bits(decode_total(total));
@@ -340,9 +343,9 @@ __device__ __forceinline__ void build_sign_table(uint8_t *tab, int tid)
     }
 }
 
-template <int Q, int Z, int LDS_STEPS>
+template <int Q, int Z, int LDS_STEPS, int NB>
 __device__ __forceinline__ void compute_table(const TileRegs<Q, Z, 1> &cur, const uint8_t *xs_buf, const uint8_t *my_tab,
-                                              int r, int h, f32x4 (&acc)[2])
+                                              int r, int h, f32x4 (&acc)[NB][2])
 {
     // chunk order, then the 4 x 4 dword transpose across the lanes r, r+16, r+32, r+48:
     // wb[t][i][B] = chunks 4h .. 4h+3 of (row 16t + r, block B, plane i)
@@ -359,6 +362,7 @@ __device__ __forceinline__ void compute_table(const TileRegs<Q, Z, 1> &cur, cons
             const auto f13 = __builtin_amdgcn_permlane32_swap(e01[1], e23[1], false, false);
             wb[t][i][0] = f02[0]; wb[t][i][1] = f13[0]; wb[t][i][2] = f02[1]; wb[t][i][3] = f13[1];
         }
+    // batch column 16 nb + r of the staged X sits in row 16 nb + r of the buffer
     const uint8_t *xb = xs_buf + r * kXPitchBytes + h * 64;
     const u32x4 ones = {0x3c003c00u, 0x3c003c00u, 0x3c003c00u, 0x3c003c00u};
 #pragma unroll
@@ -370,36 +374,66 @@ __device__ __forceinline__ void compute_table(const TileRegs<Q, Z, 1> &cur, cons
 #pragma unroll
             for (int e = 0; e < Q + Z; ++e)
                 sc[j][e] = (uint32_t)__builtin_amdgcn_ds_bpermute(4 * (16 * B + 4 * h + j), (int)cur.scales[e]);
-        f32x4 C[2][Q];
-        f32x4 Cz = {0.f, 0.f, 0.f, 0.f};
+        f32x4 C[NB][2][Q];
+        f32x4 Cz[NB];
 #pragma unroll
-        for (int t = 0; t < 2; ++t)
+        for (int nb = 0; nb < NB; ++nb) {
+            Cz[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int i = 0; i < Q; ++i) C[t][i] = f32x4{0.f, 0.f, 0.f, 0.f};
+            for (int t = 0; t < 2; ++t)
 #pragma unroll
-        for (int s = 0; s < 4; ++s) {
-            const f16x8 bx = *reinterpret_cast<const f16x8 *>(xb + (16 * B + s) * 16);
+                for (int i = 0; i < Q; ++i) C[nb][t][i] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+        // The +-1.0 operands of a step serve every group of 16 batch columns.  With four groups a
+        // wave runs alone on its SIMD (registers, LDS), so nothing else hides the LDS latency: the
+        // operands of step s+1 are requested before the MFMAs of step s are issued (with one or two
+        // groups two waves share a SIMD and the extra registers of that pipelining would cost one).
+        constexpr bool kPipelined = NB == 4;
+        auto fetch = [&](int s, f16x8 (&a)[2][Q], f16x8 (&bx)[NB]) {
 #pragma unroll
             for (int t = 0; t < 2; ++t)
 #pragma unroll
                 for (int i = 0; i < Q; ++i) {
                     const uint32_t w = wb[t][i][B];
-                    f16x8 a;
                     if (s < LDS_STEPS) {
                         const uint32_t byte = (w >> (8 * s)) & 0xffu;
-                        a = *reinterpret_cast<const f16x8 *>(my_tab + byte * (16 * kTabCopies));
+                        a[t][i] = *reinterpret_cast<const f16x8 *>(my_tab + byte * (16 * kTabCopies));
                     } else {
                         const uint32_t wn = ~w, wn4 = wn >> 4;
-                        if (s == 0) a = expand_byte<0>(wn, wn4, 0x3c003c00u);
-                        if (s == 1) a = expand_byte<1>(wn, wn4, 0x3c003c00u);
-                        if (s == 2) a = expand_byte<2>(wn, wn4, 0x3c003c00u);
-                        if (s == 3) a = expand_byte<3>(wn, wn4, 0x3c003c00u);
+                        if (s == 0) a[t][i] = expand_byte<0>(wn, wn4, 0x3c003c00u);
+                        if (s == 1) a[t][i] = expand_byte<1>(wn, wn4, 0x3c003c00u);
+                        if (s == 2) a[t][i] = expand_byte<2>(wn, wn4, 0x3c003c00u);
+                        if (s == 3) a[t][i] = expand_byte<3>(wn, wn4, 0x3c003c00u);
                     }
-                    C[t][i] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, bx, C[t][i], 0, 0, 0);
                 }
-            if (Z) Cz = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, ones), bx, Cz, 0, 0, 0);
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+                bx[nb] = *reinterpret_cast<const f16x8 *>(xb + nb * 16 * kXPitchBytes + (16 * B + s) * 16);
+        };
+        f16x8 abuf[2][2][Q], bbuf[2][NB];
+        fetch(0, abuf[0], bbuf[0]);
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const int cb = s & 1;
+            if (kPipelined) {
+                if (s + 1 < 4) fetch(s + 1, abuf[cb ^ 1], bbuf[cb ^ 1]);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+#pragma unroll
+                    for (int i = 0; i < Q; ++i)
+                        C[nb][t][i] = __builtin_amdgcn_mfma_f32_16x16x32_f16(abuf[cb][t][i], bbuf[cb][nb], C[nb][t][i], 0, 0, 0);
+                if (Z)
+                    Cz[nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, ones), bbuf[cb][nb], Cz[nb],
+                                                                    0, 0, 0);
+            }
+            if (kPipelined) __builtin_amdgcn_sched_barrier(0);
+            else if (s + 1 < 4) fetch(s + 1, abuf[cb ^ 1], bbuf[cb ^ 1]);  // left to the compiler's schedule
         }
-        // acc[t][j] += alpha_i(row 16t + 4h + j, block B) * C[t][i][j]  (+ z * column sums)
+        // acc[nb][t][j] += alpha_i(row 16t + 4h + j, block B) * C[nb][t][i][j]  (+ z * column sums)
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
@@ -409,7 +443,9 @@ __device__ __forceinline__ void compute_table(const TileRegs<Q, Z, 1> &cur, cons
                     const int e = t * (Q + Z) + c;  // half index in the lane's scale record
                     const uint32_t pair = sc[j][e >> 1];
                     const float v = half_bits_to_float((e & 1) ? (pair >> 16) : (pair & 0xffffu));
-                    acc[t][j] = fmaf(v, c < Q ? C[t][c < Q ? c : 0][j] : Cz[j], acc[t][j]);
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb)
+                        acc[nb][t][j] = fmaf(v, c < Q ? C[nb][t][c < Q ? c : 0][j] : Cz[nb][j], acc[nb][t][j]);
                 }
             }
     }
@@ -418,11 +454,17 @@ __device__ __forceinline__ void compute_table(const TileRegs<Q, Z, 1> &cur, cons
 // ---------------------------------------------------------------------------------
 // the kernel
 // ---------------------------------------------------------------------------------
-template <int Q, int Z, int SUB, int VER, int LDS_STEPS>
+// NB = groups of 16 batch columns (1, 2 or 4; more than one only with VER 2).  With one group the
+// X slice is double-buffered in LDS; with more, the staged slice (16.6 KB per group) is single-
+// buffered: the next slice waits in registers and replaces it between two barriers.
+template <int Q, int Z, int SUB, int VER, int LDS_STEPS, int NB>
 __global__ __launch_bounds__(256) void bcq_skinny_kernel(SkinnyParams p)
 {
     static_assert(VER == 1 || SUB == 1, "the table kernel needs one scaling group per block");
-    __shared__ __attribute__((aligned(16))) uint8_t xs[2 * kXBufBytes];
+    static_assert(NB == 1 || VER == 2, "several batch groups only with the table kernel");
+    constexpr bool kDouble = NB == 1;
+    constexpr int kBuf = NB * kXBufBytes;
+    __shared__ __attribute__((aligned(16))) uint8_t xs[(kDouble ? 2 : 1) * kBuf];
     __shared__ __attribute__((aligned(16))) uint8_t tab[VER == 2 ? kTabBytes : 16];
     __shared__ float stage[4 * kStageFloats];
 
@@ -443,9 +485,9 @@ __global__ __launch_bounds__(256) void bcq_skinny_kernel(SkinnyParams p)
         cur, tile_descriptor(p.blob + ((size_t)slice * p.ntile + (active ? tile : 0)) * p.tile_bytes, p.tile_bytes, active),
         lane);
     {
-        u32x4 xr[4];
-        x_slice_load(p, xrsrc, slice, true, tid, xr);
-        x_slice_store(xs, tid, xr);
+        u32x4 xr[4 * NB];
+        x_slice_load<NB>(p, xrsrc, slice, true, tid, xr);
+        x_slice_store<NB>(xs, tid, xr);
     }
     if (VER == 2) build_sign_table(tab, tid);
     __syncthreads();
@@ -458,7 +500,9 @@ __global__ __launch_bounds__(256) void bcq_skinny_kernel(SkinnyParams p)
         const int seg_end = min(u_end, (tg + 1) * p.nslice);
         const int seg_tg = tg, seg_tile = tile;
         const bool seg_active = active;
-        f32x4 acc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+        f32x4 acc[NB][2];
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) acc[nb][0] = acc[nb][1] = f32x4{0.f, 0.f, 0.f, 0.f};
         for (; u < seg_end; ++u) {
             // the next unit of this workgroup, if any (it may be the first of the next segment)
             const bool more = u + 1 < u_end;
@@ -469,24 +513,26 @@ __global__ __launch_bounds__(256) void bcq_skinny_kernel(SkinnyParams p)
             // unconditional requests for it (empty descriptor / out-of-range offsets when there is
             // none): they stay in flight while this unit is computed
             TileRegs<Q, Z, SUB> nxt;
-            u32x4 xr[4];
+            u32x4 xr[4 * NB];
             load_tile_buf<Q, Z, SUB>(
                 nxt,
                 tile_descriptor(p.blob + ((size_t)n_slice * p.ntile + (n_active ? n_tile : 0)) * p.tile_bytes,
                                 p.tile_bytes, n_active),
                 lane);
-            x_slice_load(p, xrsrc, n_slice, more, tid, xr);
+            x_slice_load<NB>(p, xrsrc, n_slice, more, tid, xr);
 
             if (active) {
-                if constexpr (VER == 1) compute_folded<Q, Z, SUB>(cur, xs + buf * kXBufBytes, r, h, acc);
-                else compute_table<Q, Z, LDS_STEPS>(cur, xs + buf * kXBufBytes, my_tab, r, h, acc);
+                if constexpr (VER == 1) compute_folded<Q, Z, SUB>(cur, xs + buf * kBuf, r, h, acc[0]);
+                else compute_table<Q, Z, LDS_STEPS, NB>(cur, xs + buf * kBuf, my_tab, r, h, acc);
             }
+            if (!kDouble) __syncthreads();  // everyone done reading the slice that is about to be replaced
             if (more) {
-                x_slice_store(xs + (buf ^ 1) * kXBufBytes, tid, xr);
+                x_slice_store<NB>(xs + (kDouble ? (buf ^ 1) * kBuf : 0), tid, xr);
                 cur = nxt;
             }
-            tg = n_tg; slice = n_slice; tile = n_tile; active = n_active; buf ^= 1;
-            __syncthreads();  // next X slice written, everyone done reading the current one
+            tg = n_tg; slice = n_slice; tile = n_tile; active = n_active;
+            if (kDouble) buf ^= 1;
+            __syncthreads();  // next X slice written (double-buffered: and everyone done with the current one)
         }
         // this workgroup is done with the tile group: flush (the next segment's first loads are in flight)
         if (seg_active) {
@@ -496,7 +542,9 @@ __global__ __launch_bounds__(256) void bcq_skinny_kernel(SkinnyParams p)
             // the flush is not hoisted out of this loop into registers that stay live during the units)
             int flush_lane = lane;
             asm volatile("" : "+v"(flush_lane));
-            skinny_store(p, acc, seg_tile, flush_lane, stage + wave * kStageFloats, arrivals);
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+                skinny_store(p, acc[nb], seg_tile, flush_lane, stage + wave * kStageFloats, arrivals, 16 * nb);
         }
     }
 }
@@ -505,14 +553,15 @@ __global__ __launch_bounds__(256) void bcq_skinny_kernel(SkinnyParams p)
 // host side
 // ---------------------------------------------------------------------------------
 // Number of workgroups of a kernel the current device holds at once (asked once per kernel).
-template <int Q, int Z, int SUB, int VER, int LDS_STEPS>
+template <int Q, int Z, int SUB, int VER, int LDS_STEPS, int NB>
 static int resident_groups()
 {
     static int cached = 0;
     if (cached == 0) {
         int per_cu = 0, dev = 0, cus = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, bcq_skinny_kernel<Q, Z, SUB, VER, LDS_STEPS>, 256, 0) !=
-                hipSuccess || per_cu < 1)
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, bcq_skinny_kernel<Q, Z, SUB, VER, LDS_STEPS, NB>, 256,
+                                                         0) != hipSuccess ||
+            per_cu < 1)
             per_cu = 1;
         if (hipGetDevice(&dev) != hipSuccess ||
             hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
@@ -524,29 +573,35 @@ static int resident_groups()
 
 // Grid size: `parts` > 0: that many workgroups per tile group (a K split); `parts` < 0: -parts
 // workgroups; 0: as many workgroups as are resident.
-template <int Q, int Z, int SUB, int VER, int LDS_STEPS>
+template <int Q, int Z, int SUB, int VER, int LDS_STEPS, int NB>
 static hipError_t launch_skinny_one(const SkinnyParams &p, int parts, bool single_slice, hipStream_t stream)
 {
     long long groups = parts > 0 ? (long long)parts * p.ntg
-                                 : parts < 0 ? -(long long)parts : resident_groups<Q, Z, SUB, VER, LDS_STEPS>();
+                                 : parts < 0 ? -(long long)parts : resident_groups<Q, Z, SUB, VER, LDS_STEPS, NB>();
     if (groups > p.units) groups = p.units;
     if (single_slice) groups = p.ntg;  // no workspace: one unit per tile group, nothing to combine
     if (groups < 1) groups = 1;
-    hipLaunchKernelGGL((bcq_skinny_kernel<Q, Z, SUB, VER, LDS_STEPS>), dim3((unsigned)groups), dim3(256), 0, stream, p);
+    hipLaunchKernelGGL((bcq_skinny_kernel<Q, Z, SUB, VER, LDS_STEPS, NB>), dim3((unsigned)groups), dim3(256), 0, stream,
+                       p);
     return hipGetLastError();
 }
 
+// One launch for up to 16 NB batch columns; p.X / p.Y / p.accum / p.batch describe exactly those.
 template <int Q, int Z>
-static hipError_t launch_skinny_qz(const SkinnyParams &p, int parts, bool single_slice, int sub, int version,
+static hipError_t launch_skinny_qz(const SkinnyParams &p, int nb, int parts, bool single_slice, int sub, int version,
                                    int lds_steps, hipStream_t stream)
 {
-    if (sub == 2) return launch_skinny_one<Q, Z, 2, 1, 0>(p, parts, single_slice, stream);
-    if (sub == 4) return launch_skinny_one<Q, Z, 4, 1, 0>(p, parts, single_slice, stream);
-    if (version == 1) return launch_skinny_one<Q, Z, 1, 1, 0>(p, parts, single_slice, stream);
+    if (sub == 2) return launch_skinny_one<Q, Z, 2, 1, 0, 1>(p, parts, single_slice, stream);
+    if (sub == 4) return launch_skinny_one<Q, Z, 4, 1, 0, 1>(p, parts, single_slice, stream);
+    if (version == 1) return launch_skinny_one<Q, Z, 1, 1, 0, 1>(p, parts, single_slice, stream);
+    if constexpr (Q <= 3) {  // with four planes, four column groups do not fit the register file
+        if (nb == 4) return launch_skinny_one<Q, Z, 1, 2, 4, 4>(p, parts, single_slice, stream);
+    }
+    if (nb == 2) return launch_skinny_one<Q, Z, 1, 2, 4, 2>(p, parts, single_slice, stream);
     // all four MFMA steps of a block from the LDS table measured fastest; 3 (one step expanded in
     // registers) is kept as the alternative for tuning runs
-    return lds_steps == 3 ? launch_skinny_one<Q, Z, 1, 2, 3>(p, parts, single_slice, stream)
-                          : launch_skinny_one<Q, Z, 1, 2, 4>(p, parts, single_slice, stream);
+    return lds_steps == 3 ? launch_skinny_one<Q, Z, 1, 2, 3, 1>(p, parts, single_slice, stream)
+                          : launch_skinny_one<Q, Z, 1, 2, 4, 1>(p, parts, single_slice, stream);
 }
 
 hipError_t launch_skinny(const Geom &g, const void *packed, const uint16_t *X, int ldx, uint16_t *Y, int ldy,
@@ -554,9 +609,7 @@ hipError_t launch_skinny(const Geom &g, const void *packed, const uint16_t *X, i
 {
     SkinnyParams p;
     p.blob = static_cast<const uint8_t *>(packed);
-    p.X = X; p.Y = Y;
-    p.accum = static_cast<unsigned long long *>(workspace);
-    p.M = g.M; p.N = g.N; p.Mp = g.Mp; p.batch = batch; p.ldx = ldx; p.ldy = ldy;
+    p.M = g.M; p.N = g.N; p.Mp = g.Mp; p.ldx = ldx; p.ldy = ldy;
     p.ntile = g.ntile; p.nslice = g.nslice; p.ntg = (g.ntile + 3) / 4;
     const long long units = (long long)p.ntg * g.nslice;
     if (units > 0x7fffffffLL) return hipErrorInvalidValue;
@@ -566,17 +619,33 @@ hipError_t launch_skinny(const Geom &g, const void *packed, const uint16_t *X, i
     const int parts = tuning.skinny_parts > 0 ? tuning.skinny_parts : -tuning.workgroups;
     const bool single = workspace == nullptr;  // only reachable for a single column slice
     const int sub = g.sub, ver = tuning.skinny_version, steps = tuning.skinny_lds_steps;
-    switch (g.q * 2 + g.z) {
-        case 2: return launch_skinny_qz<1, 0>(p, parts, single, sub, ver, steps, stream);
-        case 3: return launch_skinny_qz<1, 1>(p, parts, single, sub, ver, steps, stream);
-        case 4: return launch_skinny_qz<2, 0>(p, parts, single, sub, ver, steps, stream);
-        case 5: return launch_skinny_qz<2, 1>(p, parts, single, sub, ver, steps, stream);
-        case 6: return launch_skinny_qz<3, 0>(p, parts, single, sub, ver, steps, stream);
-        case 7: return launch_skinny_qz<3, 1>(p, parts, single, sub, ver, steps, stream);
-        case 8: return launch_skinny_qz<4, 0>(p, parts, single, sub, ver, steps, stream);
-        case 9: return launch_skinny_qz<4, 1>(p, parts, single, sub, ver, steps, stream);
+    // Up to 64 batch columns in one pass over the weights with the table kernel (the +-1 operands are
+    // shared by the groups of 16 columns); the kernel that folds alpha into A handles 16 columns per
+    // launch, so wider batches take one pass per 16 columns there.
+    const bool wide_ok = sub == 1 && ver != 1;
+    const int widest = g.q <= 3 ? 64 : 32;
+    const int cols_per_launch = wide_ok ? (batch > 32 ? widest : batch > 16 ? 32 : 16) : 16;
+    for (int col0 = 0; col0 < batch; col0 += cols_per_launch) {
+        const int cols = batch - col0 < cols_per_launch ? batch - col0 : cols_per_launch;
+        p.X = X + (size_t)col0 * ldx;
+        p.Y = Y + (size_t)col0 * ldy;
+        p.accum = static_cast<unsigned long long *>(workspace) + (workspace ? (size_t)col0 * g.Mp : 0);
+        p.batch = cols;
+        const int nb = cols > 32 ? 4 : cols > 16 ? 2 : 1;
+        hipError_t e = hipErrorInvalidValue;
+        switch (g.q * 2 + g.z) {
+            case 2: e = launch_skinny_qz<1, 0>(p, nb, parts, single, sub, ver, steps, stream); break;
+            case 3: e = launch_skinny_qz<1, 1>(p, nb, parts, single, sub, ver, steps, stream); break;
+            case 4: e = launch_skinny_qz<2, 0>(p, nb, parts, single, sub, ver, steps, stream); break;
+            case 5: e = launch_skinny_qz<2, 1>(p, nb, parts, single, sub, ver, steps, stream); break;
+            case 6: e = launch_skinny_qz<3, 0>(p, nb, parts, single, sub, ver, steps, stream); break;
+            case 7: e = launch_skinny_qz<3, 1>(p, nb, parts, single, sub, ver, steps, stream); break;
+            case 8: e = launch_skinny_qz<4, 0>(p, nb, parts, single, sub, ver, steps, stream); break;
+            case 9: e = launch_skinny_qz<4, 1>(p, nb, parts, single, sub, ver, steps, stream); break;
+        }
+        if (e != hipSuccess) return e;
     }
-    return hipErrorInvalidValue;
+    return hipSuccess;
 }
 
 }  // namespace bcq

@@ -113,7 +113,7 @@ def test_skinny_argument_checks():
     ok = 0x1000
     f = lambda ldx, ldy, b: L.bcq_gemm_skinny(ctypes.byref(d), ok, ok, ldx, ok, ldy, b, ok, None)
     assert f(1024, 64, 0) == B.BCQ_ERR_INVALID_ARG
-    assert f(1024, 64, 17) == B.BCQ_ERR_INVALID_ARG
+    assert f(1024, 64, B.BCQ_MAX_BATCH + 1) == B.BCQ_ERR_INVALID_ARG
     assert f(1016, 64, 2) == B.BCQ_ERR_INVALID_ARG     # ldx < N
     assert f(1028, 64, 2) == B.BCQ_ERR_INVALID_ARG     # ldx not a multiple of 8
     assert f(1024, 63, 2) == B.BCQ_ERR_INVALID_ARG     # ldy < M

@@ -299,3 +299,25 @@ def test_graph_replay_matches_eager():
         # eager work of the program between replays
         assert torch.equal(pl.gemm_skinny(X), Y_eager)
         torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("batch", [17, 24, 32, 33, 50, 64])
+@pytest.mark.parametrize("q,offset,group", [(3, False, 128), (2, True, 128), (4, True, 256), (3, True, 64)])
+def test_wide_batches(batch, q, offset, group):
+    """17..64 activation vectors: the table kernel shares the expanded operands between groups of 16
+    columns (q <= 3: up to 64 per pass, q = 4: 32); groups of 64 columns take one pass per 16."""
+    _run_case(203, 2560, q, group, offset, batch=batch, seed=batch + q)
+
+
+def test_wide_batch_exact_and_strided():
+    L = bcq_synth.make_exact_layer(150, 3072, 3, group=128, offset=True, batch=40, seed=77)
+    pl = U.upload_and_pack(L, max_batch=40)
+    expect = ref.gemm(L.planes, L.alpha, L.offset, L.x).astype(np.float16).astype(np.float64)
+    X = torch.zeros((40, L.N + 64), dtype=torch.float16, device="cuda")
+    X[:, :L.N] = U.x_dev(L)
+    Y = torch.full((40, L.M + 10), 3.0, dtype=torch.float16, device="cuda")
+    bcq.gemm_skinny(pl.desc, pl.packed, X, X.stride(0), Y, Y.stride(0), 40, pl.workspace)
+    torch.cuda.synchronize()
+    assert np.array_equal(Y[:, :L.M].cpu().numpy().astype(np.float64), expect)
+    assert torch.all(Y[:, L.M:] == 3.0)
+    assert not pl.workspace.cpu().numpy().any()
