@@ -201,7 +201,7 @@ def main():
         # costs the same for any batch -- hence the low fraction at small batch.
         flop = 2.0 * Q * dom["M"] * dom["N"] * B
         tfl = flop / (dom["us_per_gemv"] * 1e-6) / 1e12
-        roofline = dict(bound="mfma", kernel="bcq_skinny2_kernel (q=%d, %s, group 128, batch %d) on %dx%d"
+        roofline = dict(bound="mfma", kernel="bcq_skinny_kernel (q=%d, %s, group 128, batch %d) on %dx%d"
                                              % (Q, "offset" if args.offset else "no offset", B, dom["M"], dom["N"]),
                         achieved=round(tfl, 2), peak=2500.0, unit="TFLOP/s", frac=round(tfl / 2500.0, 4),
                         flop_per_launch=flop, us_per_launch=dom["us_per_gemv"], traffic=None,
