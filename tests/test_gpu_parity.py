@@ -321,3 +321,13 @@ def test_wide_batch_exact_and_strided():
     assert np.array_equal(Y[:, :L.M].cpu().numpy().astype(np.float64), expect)
     assert torch.all(Y[:, L.M:] == 3.0)
     assert not pl.workspace.cpu().numpy().any()
+
+
+def test_maximum_column_count():
+    """N = 523776 = 1023 column slices, the most the 10-bit arrival count of the split-K word holds
+    (one more slice is refused by the descriptor check): GEMV and skinny kernel."""
+    N = 1023 * 512
+    d = bcq.Desc(40, N + 512, 2, 128, 0, 0)
+    assert bcq.packed_bytes(d) == 0
+    _run_case(40, N, 2, 128, True, seed=3)
+    _run_case(40, N, 2, 128, True, batch=3, seed=4)
