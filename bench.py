@@ -193,6 +193,14 @@ def main():
                                weight_GBps=round(layers[name]["bytes"] / us / 1e3, 1),
                                pct_of_hbm_peak=round(layers[name]["bytes"] / us / 1e3 / HBM_PEAK_GBS * 100, 2))
     dom = per_layer[DOMINANT]
+    # what a kernel that only reads the same bytes reaches (bcq_read_probe on the dominant layer's blobs)
+    sink = torch.empty(bcq.binding.read_probe_sink_bytes(), dtype=torch.uint8, device=dev)
+    dom_ent = layers[DOMINANT]
+    nbytes_blob = dom_ent["pl"].packed.numel()
+    t = timed(lambda i: bcq.read_probe(dom_ent["copies"][i % n_copies], nbytes_blob, sink), args.steps, args.warmup + 2)
+    probe_us = t / args.steps * 1e6
+    read_probe = dict(bytes=nbytes_blob, us=round(probe_us, 3), GBps=round(nbytes_blob / probe_us / 1e3, 1),
+                      what="plain streaming read of the dominant layer's packed weights (no arithmetic)")
     achieved = dom["weight_bytes"] / (dom["us_per_gemv"] * 1e-6) / 1e9
     if B > 1:
         # The single-pass skinny kernel contracts on the matrix cores (binary16 in, fp32 accumulate):
@@ -253,7 +261,7 @@ def main():
                                   ", outlier channels" if args.outliers else "", B, n_copies), "launches_per_step": len(LAYERS),
                    "weight_bytes_per_step": total_bytes, "launch": "graph" if not args.no_graph else "eager"},
         "pct_of_hbm_peak": round(value_gbs / HBM_PEAK_GBS * 100, 2),
-        "layers": per_layer, "roofline": roofline, "cpu_baseline": cpu, "parity": parity,
+        "layers": per_layer, "roofline": roofline, "read_probe": read_probe, "cpu_baseline": cpu, "parity": parity,
         "context": PAPER_CONTEXT,
     }
     print(json.dumps(out))

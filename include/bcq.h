@@ -189,8 +189,7 @@ bcq_status bcq_read_probe(const void *buf, size_t bytes, void *sink, void *strea
  * batch >= 2), "skinny_version" (1 = the kernel that folds alpha into the
  * matrix-core operand, 2 = the kernel that takes +-1 operands from an LDS table;
  * groups of 32/64 always use 1), "skinny_lds_steps" (3 or 4, kernel 2 only);
- * 0 = automatic.  "probe" = 1 is for timing experiments only and makes the
- * GEMV's results meaningless: every tile re-reads the first tile (no HBM traffic).
+ * 0 = automatic.
  * Unknown names or values return BCQ_ERR_INVALID_ARG.
  */
 bcq_status bcq_set_option(const char *name, int32_t value);

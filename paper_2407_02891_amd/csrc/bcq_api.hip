@@ -182,10 +182,6 @@ bcq_status bcq_set_option(const char *name, int32_t value)
         g_tuning.skinny_lds_steps = value;
         return BCQ_OK;
     }
-    if (strcmp(name, "probe") == 0 && value <= 1) {
-        g_tuning.probe = value;
-        return BCQ_OK;
-    }
     return BCQ_ERR_INVALID_ARG;
 }
 

@@ -55,21 +55,8 @@ struct GemvParams {
     int ntile, nslice;
     int parts, big_slices;  // slices [0, big_slices) have parts+1 workgroups, the others parts
     unsigned tile_bytes;
-#ifdef BCQ_TRACE
-    unsigned long long *trace;  // per wave 16 timestamps (100 MHz), development builds only
-#endif
 };
 
-#ifdef BCQ_TRACE
-#define BCQ_TRACE_DECL unsigned long long trace_t[16] = {0}; int trace_n = 0;
-#define BCQ_TRACE_POINT() do { if (trace_n < 16) trace_t[trace_n++] = wall_clock64(); } while (0)
-#define BCQ_TRACE_DUMP() do { if (p.trace && lane == 0) for (int i = 0; i < 16; ++i) \
-        p.trace[((size_t)blockIdx.x * NW + wave) * 16 + i] = trace_t[i]; } while (0)
-#else
-#define BCQ_TRACE_DECL
-#define BCQ_TRACE_POINT() do {} while (0)
-#define BCQ_TRACE_DUMP() do {} while (0)
-#endif
 
 // One table lookup: byte `n` of plane word `w` is the index, byte `n` of `rv`
 // is 4*chunk; the LDS byte address is index*256 + 4*chunk.
@@ -121,8 +108,6 @@ __global__ __launch_bounds__(NW * 64) void bcq_gemv_kernel(GemvParams p)
 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
-    BCQ_TRACE_DECL
-    BCQ_TRACE_POINT();  // start
     int slice, part, parts;
     {
         const int big_groups = p.big_slices * (p.parts + 1);
@@ -180,9 +165,7 @@ __global__ __launch_bounds__(NW * 64) void bcq_gemv_kernel(GemvParams p)
             for (int a = 0; a < 8; ++a) lut[(wave * IPW + m * 8 + a) * 64 + lane] = lo[a] + mid;
         }
     }
-    BCQ_TRACE_POINT();  // tables written
     __syncthreads();
-    BCQ_TRACE_POINT();  // barrier passed
 
     // ---- per-lane constants ----------------------------------------------------
     const int r = lane & 15, h = lane >> 4;
@@ -222,7 +205,6 @@ __global__ __launch_bounds__(NW * 64) void bcq_gemv_kernel(GemvParams p)
 
     for (int tile = t_begin; tile < t_end; ++tile) {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // (a)
-        BCQ_TRACE_POINT();  // tile arrived
         if (split_k && lane < 32) {
             if (pend_tile >= 0) complete_row(p, pend_tile * kTileRows + lane, pend_old + pend_mine);  // (b)
             pend_tile = held_tile;
@@ -257,7 +239,6 @@ __global__ __launch_bounds__(NW * 64) void bcq_gemv_kernel(GemvParams p)
             acc[t] = a;
         }
         const float out = (lane & 16) ? acc[1] : acc[0];  // lanes 0..31 <-> rows 0..31 of the tile
-        BCQ_TRACE_POINT();  // tile computed
         if (split_k) {
             held = out;
             held_tile = tile;
@@ -279,8 +260,6 @@ __global__ __launch_bounds__(NW * 64) void bcq_gemv_kernel(GemvParams p)
             complete_row(p, pend_tile * kTileRows + lane, pend_old + pend_mine);
         }
     }
-    BCQ_TRACE_POINT();  // end
-    BCQ_TRACE_DUMP();
 }
 
 // ---------------------------------------------------------------------------------
@@ -335,10 +314,7 @@ hipError_t launch_gemv(const Geom &g, const void *packed, const uint16_t *x, uin
     p.accum = static_cast<unsigned long long *>(workspace);
     p.M = g.M; p.N = g.N; p.Mp = g.Mp;
     p.ntile = g.ntile; p.nslice = g.nslice;
-    p.tile_bytes = (t.probe & 1) ? 0u : g.tile_bytes;
-#ifdef BCQ_TRACE
-    p.trace = t.trace;
-#endif
+    p.tile_bytes = g.tile_bytes;
     const int key = g.q * 2 + g.z;
     switch (key) {
         case 2: return launch_qz<1, 0>(p, nw, g.sub, groups, stream);
@@ -359,14 +335,23 @@ hipError_t launch_gemv(const Geom &g, const void *packed, const uint16_t *x, uin
 __global__ __launch_bounds__(256) void read_probe_kernel(const u32x4 *__restrict__ buf, size_t n16,
                                                          uint32_t *__restrict__ sink)
 {
-    // each workgroup reads one contiguous span, 4 KB per wave per step
+    // each workgroup reads one contiguous span; each wave keeps 4 KB (4 loads of 16 B per lane) in flight
+    constexpr int U = 4;
     size_t per_block = (n16 + gridDim.x - 1) / gridDim.x;
-    size_t begin = (size_t)blockIdx.x * per_block;
-    size_t end = begin + per_block < n16 ? begin + per_block : n16;
+    per_block = (per_block + 256 * U - 1) / (256 * U) * (256 * U);
+    const size_t begin = (size_t)blockIdx.x * per_block;
+    const size_t end = begin + per_block < n16 ? begin + per_block : n16;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     uint32_t acc = 0;
-    for (size_t i = begin + threadIdx.x; i < end; i += 256) {
-        u32x4 v = __builtin_nontemporal_load(buf + i);
-        acc ^= v.x ^ v.y ^ v.z ^ v.w;
+    for (size_t i = begin + wave * (64 * U) + lane; i < end; i += 256 * U) {
+        u32x4 v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const size_t idx = i + u * 64;
+            v[u] = idx < end ? __builtin_nontemporal_load(buf + idx) : u32x4{0u, 0u, 0u, 0u};
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) acc ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
     }
     acc ^= __shfl_xor(acc, 32, 64);
     acc ^= __shfl_xor(acc, 16, 64);
@@ -375,7 +360,7 @@ __global__ __launch_bounds__(256) void read_probe_kernel(const u32x4 *__restrict
     acc ^= __shfl_xor(acc, 2, 64);
     acc ^= __shfl_xor(acc, 1, 64);
     __shared__ uint32_t part[4];
-    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = acc;
+    if (lane == 0) part[wave] = acc;
     __syncthreads();
     if (threadIdx.x == 0) sink[blockIdx.x] = part[0] ^ part[1] ^ part[2] ^ part[3];
 }

@@ -29,10 +29,6 @@ struct GemvTuning {
     int skinny_version = 0;    // 1 = the first skinny kernel (alpha folded into A) also where the second applies
     int skinny_lds_steps = 0;  // second skinny kernel: MFMA steps per block whose A operand comes from the
                                // LDS table, 3 or 4 (0 = automatic = 4)
-    int probe = 0;      // timing experiment (wrong results): 1 = every tile re-reads tile 0
-#ifdef BCQ_TRACE
-    unsigned long long *trace = nullptr;  // development builds: per-wave timestamps
-#endif
 };
 hipError_t launch_gemv(const Geom &g, const void *packed, const uint16_t *x, uint16_t *y,
                        void *workspace, const GemvTuning &tuning, hipStream_t stream);
@@ -41,7 +37,7 @@ hipError_t launch_skinny(const Geom &g, const void *packed, const uint16_t *X, i
                          int batch, void *workspace, const GemvTuning &tuning, hipStream_t stream);
 hipError_t launch_read_probe(const void *buf, size_t bytes, void *sink, hipStream_t stream);
 
-constexpr int kProbeBlocks = 2048;
+constexpr int kProbeBlocks = 512;  // the GEMV's grid: two workgroups per CU
 
 // Grid size the GEMV uses when none is forced.
 int auto_workgroups(const Geom &g, int waves_per_group);
