@@ -60,6 +60,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=12)
     ap.add_argument("--workload", choices=sorted(WORKLOADS), default="opt30b")
     ap.add_argument("--q", type=int, choices=(2, 3), default=3, help="number of sign planes")
+    ap.add_argument("--rowwise", action="store_true",
+                    help="one scaling group per row (group = N, the paper's setting) instead of groups of 128")
     ap.add_argument("--offset", action="store_true", help="add the per-group fp16 offset term (N(0, 0.01))")
     ap.add_argument("--outliers", action="store_true", help="scale 1 %% of the activation channels by 20")
     ap.add_argument("--batch", type=int, default=1,
@@ -103,10 +105,11 @@ def main():
     total_bytes = 0
     for name, parts, N in LAUNCHES:
         M = sum(rows for _, rows in parts)
-        pl = bcq.PackedLayer(M, N, Q, GROUP, args.offset, max_batch=B)
+        group = N if args.rowwise else GROUP
+        pl = bcq.PackedLayer(M, N, Q, group, args.offset, max_batch=B)
         subs, row0, nbytes = [], 0, 0
         for k, (pname, rows) in enumerate(parts):  # each projection from its own tensors
-            L = bcq_synth.make_layer(rows, N, Q, group=GROUP, offset=args.offset, batch=B, seed=k,
+            L = bcq_synth.make_layer(rows, N, Q, group=group, offset=args.offset, batch=B, seed=k,
                                      outlier_frac=0.01 if args.outliers else 0.0)
             codes = to_dev(L.codes())
             alpha = to_dev(L.alpha.view(np.uint16).astype(np.int16)).view(torch.float16)
@@ -209,22 +212,24 @@ def main():
         # costs the same for any batch -- hence the low fraction at small batch.
         flop = 2.0 * Q * dom["M"] * dom["N"] * B
         tfl = flop / (dom["us_per_gemv"] * 1e-6) / 1e12
-        roofline = dict(bound="mfma", kernel="bcq_skinny_kernel (q=%d, %s, group 128, batch %d) on %dx%d"
-                                             % (Q, "offset" if args.offset else "no offset", B, dom["M"], dom["N"]),
+        roofline = dict(bound="mfma", kernel="bcq_skinny_kernel (q=%d, %s, %s, batch %d) on %dx%d"
+                                             % (Q, "offset" if args.offset else "no offset",
+                                                "row-wise scales" if args.rowwise else "group 128", B, dom["M"], dom["N"]),
                         achieved=round(tfl, 2), peak=2500.0, unit="TFLOP/s", frac=round(tfl / 2500.0, 4),
                         flop_per_launch=flop, us_per_launch=dom["us_per_gemv"], traffic=None,
                         limiter="LDS read bandwidth of the sign-expansion table",
                         weight_GBps=dom["weight_GBps"])
     else:
         roofline = dict(bound="hbm",
-                        kernel="bcq_gemv_kernel (q=%d, %s, group 128) on %dx%d"
-                               % (Q, "offset" if args.offset else "no offset", dom["M"], dom["N"]),
+                        kernel="bcq_gemv_kernel (q=%d, %s, %s) on %dx%d"
+                               % (Q, "offset" if args.offset else "no offset",
+                                  "row-wise scales" if args.rowwise else "group 128", dom["M"], dom["N"]),
                         achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s",
                         frac=round(achieved / HBM_PEAK_GBS, 4), bytes_per_launch=dom["weight_bytes"],
                         us_per_launch=dom["us_per_gemv"], traffic=None)
     # HBM bytes per launch measured separately with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE); see profiles/
     traffic_file = os.path.join(ROOT, "profiles", "bcq_gemv_opt30b_q3_hbm_traffic.md")
-    if os.path.exists(traffic_file) and args.workload == "opt30b" and Q == 3 and B == 1 and not args.offset:
+    if os.path.exists(traffic_file) and args.workload == "opt30b" and Q == 3 and B == 1 and not args.offset and not args.rowwise:
         for line in open(traffic_file):
             if line.startswith("hbm_bytes_per_launch_fc2"):
                 roofline["traffic"] = float(line.split("=")[1])
@@ -256,8 +261,9 @@ def main():
         "value": round(value_gbs, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16 activations, 1-bit planes x%d, f32 accumulate" % Q, "data": "synthetic",
-        "config": {"workload": "%s, q=%d, group=128%s%s, batch=%d, cold weights (%d rotating copies)"
-                               % (WORKLOAD_TEXT, Q, ", with offset" if args.offset else "",
+        "config": {"workload": "%s, q=%d, %s%s%s, batch=%d, cold weights (%d rotating copies)"
+                               % (WORKLOAD_TEXT, Q, "row-wise scales (group=N)" if args.rowwise else "group=128",
+                                  ", with offset" if args.offset else "",
                                   ", outlier channels" if args.outliers else "", B, n_copies), "launches_per_step": len(LAYERS),
                    "weight_bytes_per_step": total_bytes, "launch": "graph" if not args.no_graph else "eager"},
         "pct_of_hbm_peak": round(value_gbs / HBM_PEAK_GBS * 100, 2),

@@ -43,7 +43,7 @@ typedef enum {
 } bcq_status;
 
 /* Version of the opaque packed layout written by bcq_pack. */
-#define BCQ_LAYOUT_VERSION 1
+#define BCQ_LAYOUT_VERSION 2
 
 /* Largest batch bcq_gemm_skinny accepts. */
 #define BCQ_MAX_BATCH 64

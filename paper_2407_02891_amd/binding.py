@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libbcq.so")
 
 BCQ_OK, BCQ_ERR_INVALID_ARG, BCQ_ERR_UNSUPPORTED, BCQ_ERR_WORKSPACE, BCQ_ERR_HIP = range(5)
-BCQ_LAYOUT_VERSION = 1
+BCQ_LAYOUT_VERSION = 2
 BCQ_MAX_BATCH = 64
 
 EXPORTS = ["bcq_packed_bytes", "bcq_workspace_bytes", "bcq_workspace_init", "bcq_pack",

@@ -26,15 +26,17 @@ struct TileRegs {
     uint32_t scales[(Q + Z) * SUB];  // binary16 pairs: [t][range][c] flattened, 2*SUB*(Q+Z) halves
 };
 
+// `scale_lane` = index of the lane's scale record: the lane itself, or lane mod 16 when the
+// scales are stored once per row (see bcq_layout.h).
 template <int Q, int Z, int SUB>
-__device__ __forceinline__ void load_tile(TileRegs<Q, Z, SUB> &r, const uint8_t *tile, int lane)
+__device__ __forceinline__ void load_tile(TileRegs<Q, Z, SUB> &r, const uint8_t *tile, int lane, int scale_lane)
 {
     const u32x4 *pp = reinterpret_cast<const u32x4 *>(tile) + lane;
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
         for (int i = 0; i < Q; ++i) r.planes[t][i] = __builtin_nontemporal_load(pp + (t * Q + i) * 64);
-    const uint32_t *sp = reinterpret_cast<const uint32_t *>(tile + 2u * Q * 1024u) + lane * ((Q + Z) * SUB);
+    const uint32_t *sp = reinterpret_cast<const uint32_t *>(tile + 2u * Q * 1024u) + scale_lane * ((Q + Z) * SUB);
 #pragma unroll
     for (int c = 0; c < (Q + Z) * SUB; ++c) r.scales[c] = __builtin_nontemporal_load(sp + c);
 }
@@ -46,7 +48,8 @@ constexpr int kRawBufferFlags = 0x00020000;
 // the range returns zeros without touching memory.  Lets a loop request "the next tile, if any"
 // without a branch, so that the compiler can count the outstanding loads instead of draining them.
 template <int Q, int Z, int SUB>
-__device__ __forceinline__ void load_tile_buf(TileRegs<Q, Z, SUB> &r, __amdgpu_buffer_rsrc_t rsrc, int lane)
+__device__ __forceinline__ void load_tile_buf(TileRegs<Q, Z, SUB> &r, __amdgpu_buffer_rsrc_t rsrc, int lane,
+                                              int scale_lane)
 {
     constexpr int kNonTemporal = 2;
     const uint32_t po = 16u * lane;
@@ -55,7 +58,7 @@ __device__ __forceinline__ void load_tile_buf(TileRegs<Q, Z, SUB> &r, __amdgpu_b
 #pragma unroll
         for (int i = 0; i < Q; ++i)
             r.planes[t][i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, po + (t * Q + i) * 1024u, 0, kNonTemporal);
-    const uint32_t so = 2u * Q * 1024u + 4u * (Q + Z) * SUB * lane;
+    const uint32_t so = 2u * Q * 1024u + 4u * (Q + Z) * SUB * scale_lane;
 #pragma unroll
     for (int c = 0; c < (Q + Z) * SUB; ++c)
         r.scales[c] = __builtin_amdgcn_raw_buffer_load_b32(rsrc, so + 4u * c, 0, kNonTemporal);

@@ -55,6 +55,7 @@ struct GemvParams {
     int ntile, nslice;
     int parts, big_slices;  // slices [0, big_slices) have parts+1 workgroups, the others parts
     unsigned tile_bytes;
+    int scale_lane_mask;  // 63: one scale record per lane; 15: one per row (group = N)
 };
 
 
@@ -135,7 +136,7 @@ __global__ __launch_bounds__(NW * 64) void bcq_gemv_kernel(GemvParams p)
     const int col0 = slice * kTileCols + kChunkCols * lane;  // lane = chunk
     u32x4 xr = {0u, 0u, 0u, 0u};
     if (col0 < p.N) xr = *reinterpret_cast<const u32x4 *>(p.x + col0);
-    if (t_begin < t_end) load_tile<Q, Z, SUB>(cur, tile_ptr, lane);
+    if (t_begin < t_end) load_tile<Q, Z, SUB>(cur, tile_ptr, lane, lane & p.scale_lane_mask);
 
     // ---- sign-sum tables for the 512 activations of this slice ----------------
     {
@@ -216,7 +217,7 @@ __global__ __launch_bounds__(NW * 64) void bcq_gemv_kernel(GemvParams p)
         }
         TileRegs<Q, Z, SUB> nxt;
         tile_ptr += p.tile_bytes;
-        if (tile + 1 < t_end) load_tile<Q, Z, SUB>(nxt, tile_ptr, lane);  // (d)
+        if (tile + 1 < t_end) load_tile<Q, Z, SUB>(nxt, tile_ptr, lane, lane & p.scale_lane_mask);  // (d)
 
         float acc[2];  // (e)
 #pragma unroll
@@ -315,6 +316,7 @@ hipError_t launch_gemv(const Geom &g, const void *packed, const uint16_t *x, uin
     p.M = g.M; p.N = g.N; p.Mp = g.Mp;
     p.ntile = g.ntile; p.nslice = g.nslice;
     p.tile_bytes = g.tile_bytes;
+    p.scale_lane_mask = g.scale_lanes - 1;
     const int key = g.q * 2 + g.z;
     switch (key) {
         case 2: return launch_qz<1, 0>(p, nw, g.sub, groups, stream);

@@ -21,7 +21,11 @@
 //                                      present) of (row, block kb) for byte range p of the
 //                                      lane, i.e. of scaling sub-group subgroup_of_range(p,
 //                                      r, sub); sub = 128/group splits the 128 columns when
-//                                      group < 128; the values are replicated when group > 128.
+//                                      group < 128; the values are replicated when group is
+//                                      a larger multiple of 128.
+//     When the whole row is one group (group = N, the paper's row-wise parameters) the scales
+//     do not depend on the block: the record is stored once per row, [r = 0..15][t][c], and the
+//     four lanes 16h + r read the same one (scale_lanes = 16 instead of 64).
 //
 //   blob = tiles ordered by column slice first, then by row tile, so that a
 //   workgroup, which owns one column slice, streams consecutive memory.
@@ -50,6 +54,7 @@ struct Geom {
     int sub;        // scale sub-groups per 128-column block: 128/group for group 32 or 64
                     // (unless the row is one group), else 1
     int nsc;        // binary16 scale entries per (row, block): sub * (q + z)
+    int scale_lanes;  // scale records per tile and row half: 64 (one per lane), or 16 (one per row) if group == N
     int Mp, Np;     // padded sizes
     int ntile;      // row tiles   = Mp / 32
     int nslice;     // col slices  = Np / 512
@@ -68,7 +73,8 @@ BCQ_HD inline Geom make_geom(int M, int N, int q, int group, int has_offset)
     g.ntile = g.Mp / kTileRows;
     g.nslice = g.Np / kTileCols;
     g.tile_plane_bytes = 2u * q * 64u * 16u;
-    g.tile_bytes = g.tile_plane_bytes + 64u * 2u * g.nsc * 2u;
+    g.scale_lanes = group == N ? 16 : 64;
+    g.tile_bytes = g.tile_plane_bytes + (unsigned)g.scale_lanes * 2u * g.nsc * 2u;
     return g;
 }
 

@@ -51,7 +51,7 @@ __global__ void pack_scales_kernel(Geom g, int row0, int rows, const uint16_t *_
 {
     size_t gid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (gid >= total_entries) return;
-    const unsigned per_tile = 64u * 2u * g.nsc;
+    const unsigned per_tile = (unsigned)g.scale_lanes * 2u * g.nsc;  // with 16 records per half tile, `lane` below is the row
     size_t tile_lin = gid / per_tile;
     unsigned e = (unsigned)(gid % per_tile);
     int slice = (int)(tile_lin / g.ntile), tile = (int)(tile_lin % g.ntile);
@@ -104,7 +104,7 @@ __global__ void unpack_scales_kernel(Geom g, const uint8_t *__restrict__ blob,
     int tile = row / kTileRows, t = (row % kTileRows) / 16, r = row % 16;
     // subgroup_of_range is its own inverse in its first argument
     int range = subgroup_of_range((col % kBlockCols) / (kBlockCols / g.sub), r, g.sub);
-    int lane = 16 * h + r, qz = g.q + g.z;
+    int lane = (16 * h + r) & (g.scale_lanes - 1), qz = g.q + g.z;
     const uint16_t *src = reinterpret_cast<const uint16_t *>(
         blob + tile_offset(g, slice, tile) + g.tile_plane_bytes) +
         (size_t)lane * 2 * g.nsc + (size_t)t * g.nsc + (size_t)range * qz;
@@ -130,7 +130,7 @@ hipError_t launch_pack(const Geom &g, int row0, int rows, const uint8_t *codes, 
 {
     size_t tiles = (size_t)g.nslice * g.ntile;
     size_t nd = tiles * (g.tile_plane_bytes / 4);
-    size_t ne = tiles * 64u * 2u * g.nsc;
+    size_t ne = tiles * (size_t)g.scale_lanes * 2u * g.nsc;
     hipLaunchKernelGGL(pack_planes_kernel, dim3(blocks_for(nd, 256)), dim3(256), 0, stream, g, row0, rows,
                        codes, static_cast<uint8_t *>(packed), nd);
     hipLaunchKernelGGL(pack_scales_kernel, dim3(blocks_for(ne, 256)), dim3(256), 0, stream, g, row0, rows,

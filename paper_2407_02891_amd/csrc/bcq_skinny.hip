@@ -54,6 +54,7 @@ struct SkinnyParams {
     int ntile, nslice, ntg;  // ntg = ceil(ntile / 4) tile groups (the four row tiles of a workgroup)
     int units;               // ntg * nslice work units; workgroup w owns units [w*units/G, (w+1)*units/G)
     unsigned tile_bytes;
+    int scale_lane_mask;     // 63: one scale record per lane; 15: one per row (group = N)
 };
 
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
@@ -483,7 +484,7 @@ __global__ __launch_bounds__(256) void bcq_skinny_kernel(SkinnyParams p)
     TileRegs<Q, Z, SUB> cur;
     load_tile_buf<Q, Z, SUB>(
         cur, tile_descriptor(p.blob + ((size_t)slice * p.ntile + (active ? tile : 0)) * p.tile_bytes, p.tile_bytes, active),
-        lane);
+        lane, lane & p.scale_lane_mask);
     {
         u32x4 xr[4 * NB];
         x_slice_load<NB>(p, xrsrc, slice, true, tid, xr);
@@ -518,7 +519,7 @@ __global__ __launch_bounds__(256) void bcq_skinny_kernel(SkinnyParams p)
                 nxt,
                 tile_descriptor(p.blob + ((size_t)n_slice * p.ntile + (n_active ? n_tile : 0)) * p.tile_bytes,
                                 p.tile_bytes, n_active),
-                lane);
+                lane, lane & p.scale_lane_mask);
             x_slice_load<NB>(p, xrsrc, n_slice, more, tid, xr);
 
             if (active) {
@@ -615,6 +616,7 @@ hipError_t launch_skinny(const Geom &g, const void *packed, const uint16_t *X, i
     if (units > 0x7fffffffLL) return hipErrorInvalidValue;
     p.units = (int)units;
     p.tile_bytes = g.tile_bytes;
+    p.scale_lane_mask = g.scale_lanes - 1;
     // forced grid sizes (tuning runs, tests): a K split per tile group, or a plain number of workgroups
     const int parts = tuning.skinny_parts > 0 ? tuning.skinny_parts : -tuning.workgroups;
     const bool single = workspace == nullptr;  // only reachable for a single column slice

@@ -76,6 +76,13 @@ def test_small_groups_are_sized_with_one_scale_set_per_group():
         assert bcq.packed_bytes(d) == 2 * 3 * 1024 + 64 * 2 * sub * 4 * 2
 
 
+def test_row_wise_scales_are_stored_once_per_row():
+    d = bcq.Desc(32, 1024, 3, 1024, 1, 0)        # group = N: 16 scale records per half tile instead of 64
+    assert bcq.packed_bytes(d) == 2 * (2 * 3 * 1024 + 16 * 2 * 4 * 2)
+    d = bcq.Desc(32, 1024, 3, 512, 1, 0)         # two groups per row: one record per lane
+    assert bcq.packed_bytes(d) == 2 * (2 * 3 * 1024 + 64 * 2 * 4 * 2)
+
+
 def test_pack_rows_argument_checks():
     L = bcq.lib()
     d = bcq.Desc(64, 1024, 3, 128, 0, 0)

@@ -331,3 +331,35 @@ def test_maximum_column_count():
     assert bcq.packed_bytes(d) == 0
     _run_case(40, N, 2, 128, True, seed=3)
     _run_case(40, N, 2, 128, True, batch=3, seed=4)
+
+
+@pytest.mark.parametrize("q,offset", [(3, True), (2, False), (4, True)])
+def test_row_wise_parameters(q, offset):
+    """group = N, the paper's setting (quantisation parameters fixed per row): scale records are
+    stored once per row; GEMV, both skinny kernels, wide batch, pack/unpack round trip, fused rows."""
+    for M, N in ((203, 2560), (64, 96), (100, 7168)):
+        _run_case(M, N, q, N, offset, seed=M + q)
+        _run_case(M, N, q, N, offset, batch=5, seed=M + q + 1)
+    _run_case(150, 3072, q, 3072, offset, batch=40, seed=q)
+    try:
+        bcq.set_option("skinny_version", 1)
+        _run_case(150, 3072, q, 3072, offset, batch=9, seed=q + 9)
+    finally:
+        bcq.set_option("skinny_version", 0)
+    L = bcq_synth.make_layer(77, 1120, q, group=1120, offset=offset, seed=8 + q)
+    pl = U.upload_and_pack(L)
+    codes = torch.empty((L.M, L.N), dtype=torch.uint8, device="cuda")
+    alpha = torch.empty((L.M, 1, L.q), dtype=torch.float16, device="cuda")
+    off = torch.empty((L.M, 1), dtype=torch.float16, device="cuda") if offset else None
+    bcq.unpack(pl.desc, pl.packed, codes, alpha, off)
+    torch.cuda.synchronize()
+    assert np.array_equal(codes.cpu().numpy(), L.codes())
+    assert np.array_equal(alpha.cpu().numpy().view(np.uint16), L.alpha.view(np.uint16))
+    if offset:
+        assert np.array_equal(off.cpu().numpy().view(np.uint16), L.offset.view(np.uint16))
+    fused = bcq.PackedLayer(L.M, L.N, L.q, L.group, offset)
+    fused.packed.fill_(0x5A)
+    for lo, hi in ((30, 77), (0, 30)):
+        fused.pack_rows_from(lo, *_rows_of(L, lo, hi))
+    torch.cuda.synchronize()
+    assert torch.equal(fused.packed, pl.packed)
