@@ -128,6 +128,46 @@ bcq_status bcq_from_linear(int32_t M, int32_t N, int32_t group, int32_t n_bits, 
                            void *stream);
 
 /*
+ * The quantiser itself, for one layer with row-wise parameters (Sec. II-A Eq. 1-2, Sec. II-B Eq. 5-6,
+ * Sec. II-C Eq. 7 and the algorithm closing Sec. II-D).  Offline tooling, three steps:
+ *
+ *   bcq_quant_search   per row: qbias = min w; the scale S' on `grid` equidistant points inside
+ *                      ((max-min)/(2^(n_bits+1)-1), (max-min)/(2^(n_bits-1)-1)) (Eq. 7) and the tying
+ *                      of the n_bits linear planes into q classes (Eq. 10) that minimise the output
+ *                      error d (H/2) d^T of the row, d = S' W_q + qbias - w, W_q = nearest
+ *                      representable integer of clamp(rne((w - qbias)/S')) (Eq. 5, 6).  Candidates
+ *                      are visited scale-major, tyings in lexicographic order of their classes; the
+ *                      first with the smallest error wins.
+ *   bcq_quant_gptq     the column-by-column pass with error compensation (Eq. 1-2) using those
+ *                      parameters; U is the upper Cholesky factor of the inverse (dampened) Hessian,
+ *                      H^-1 = U^T U, which the caller computes with any linear-algebra library.
+ *   bcq_from_linear_rows   bcq_from_linear with one tying per row and one scaling group per row
+ *                      (use group = N and has_offset = 1 for bcq_pack).
+ *
+ *   W   DEVICE [M][N] binary32 weights (not modified)
+ *   H   DEVICE [N][N] binary32, 2 X X^T of the calibration inputs (symmetric)
+ *   U   DEVICE [N][N] binary32, upper triangular
+ *   S, qbias DEVICE [M] binary32 (out of search, in of the others)
+ *   class_of_plane DEVICE [M][n_bits] int8: class (0..q-1) of bit i of row m (out of search)
+ *   err DEVICE [M] binary32 or NULL: the smallest error found (out)
+ *   w_int DEVICE [M][N] uint8: integers in the row's representable set (out of gptq)
+ *   codes DEVICE [M][N] uint8, alpha DEVICE [M][q] binary16, offset DEVICE [M] binary16 (out)
+ *   workspace DEVICE, bcq_quant_workspace_bytes(M, N) bytes, 16-byte aligned (scratch, no init)
+ * 2 <= n_bits <= 8, q <= n_bits, 1 <= grid <= 4096; q > 4 or N > 65536 is BCQ_ERR_UNSUPPORTED.
+ * Integer decisions are taken in binary64; the error sums and the compensation run in binary32.
+ */
+size_t bcq_quant_workspace_bytes(int32_t M, int32_t N);
+bcq_status bcq_quant_search(int32_t M, int32_t N, int32_t n_bits, int32_t q, int32_t grid, const float *W,
+                            const float *H, float *S, float *qbias, int8_t *class_of_plane, float *err,
+                            void *workspace, void *stream);
+bcq_status bcq_quant_gptq(int32_t M, int32_t N, int32_t n_bits, int32_t q, const float *W, const float *U,
+                          const float *S, const float *qbias, const int8_t *class_of_plane, uint8_t *w_int,
+                          void *workspace, void *stream);
+bcq_status bcq_from_linear_rows(int32_t M, int32_t N, int32_t n_bits, int32_t q, const int8_t *class_of_plane,
+                                const uint8_t *w_int, const float *S, const float *qbias, uint8_t *codes,
+                                uint16_t *alpha, uint16_t *offset, void *stream);
+
+/*
  * bcq_pack for a range of rows: writes the rows [row_begin, row_begin + rows) of the layer
  * `desc` describes from sources that hold ONLY those rows (codes [rows][N], alpha
  * [rows][N/group][q], offset [rows][N/group]).  Layers that are applied to the same

@@ -13,7 +13,8 @@ BCQ_LAYOUT_VERSION = 2
 BCQ_MAX_BATCH = 64
 
 EXPORTS = ["bcq_packed_bytes", "bcq_workspace_bytes", "bcq_workspace_init", "bcq_pack",
-           "bcq_pack_rows", "bcq_from_linear", "bcq_unpack", "bcq_gemv", "bcq_gemm_skinny", "bcq_read_probe_sink_bytes",
+           "bcq_pack_rows", "bcq_from_linear", "bcq_quant_workspace_bytes", "bcq_quant_search",
+           "bcq_quant_gptq", "bcq_from_linear_rows", "bcq_unpack", "bcq_gemv", "bcq_gemm_skinny", "bcq_read_probe_sink_bytes",
            "bcq_read_probe", "bcq_set_option", "bcq_status_string"]
 
 
@@ -50,6 +51,13 @@ def lib():
         L.bcq_pack_rows.restype, L.bcq_pack_rows.argtypes = i32, [dp, i32, i32, vp, vp, vp, vp, vp]
         L.bcq_from_linear.restype = i32
         L.bcq_from_linear.argtypes = [i32, i32, i32, i32, i32, ctypes.POINTER(ctypes.c_int32), vp, vp, vp, vp, vp, vp, vp]
+        L.bcq_quant_workspace_bytes.restype, L.bcq_quant_workspace_bytes.argtypes = sz, [i32, i32]
+        L.bcq_quant_search.restype = i32
+        L.bcq_quant_search.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.bcq_quant_gptq.restype = i32
+        L.bcq_quant_gptq.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.bcq_from_linear_rows.restype = i32
+        L.bcq_from_linear_rows.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]
         L.bcq_unpack.restype, L.bcq_unpack.argtypes = i32, [dp, vp, vp, vp, vp, vp]
         L.bcq_gemv.restype, L.bcq_gemv.argtypes = i32, [dp, vp, vp, vp, vp, vp]
         L.bcq_gemm_skinny.restype = i32
@@ -119,6 +127,27 @@ def from_linear(M, N, group, n_bits, q, class_of_plane, w_int, S, qbias, codes, 
     _check(lib().bcq_from_linear(int(M), int(N), int(group), int(n_bits), int(q), labels, _ptr(w_int), _ptr(S),
                                  _ptr(qbias), _ptr(codes), _ptr(alpha), _ptr(offset), _stream(stream)),
            "bcq_from_linear")
+
+
+def quant_workspace_bytes(M, N):
+    return int(lib().bcq_quant_workspace_bytes(int(M), int(N)))
+
+
+def quant_search(M, N, n_bits, q, grid, W, H, S, qbias, class_of_plane, err, workspace, stream=None):
+    _check(lib().bcq_quant_search(int(M), int(N), int(n_bits), int(q), int(grid), _ptr(W), _ptr(H), _ptr(S),
+                                  _ptr(qbias), _ptr(class_of_plane), _ptr(err), _ptr(workspace), _stream(stream)),
+           "bcq_quant_search")
+
+
+def quant_gptq(M, N, n_bits, q, W, U, S, qbias, class_of_plane, w_int, workspace, stream=None):
+    _check(lib().bcq_quant_gptq(int(M), int(N), int(n_bits), int(q), _ptr(W), _ptr(U), _ptr(S), _ptr(qbias),
+                                _ptr(class_of_plane), _ptr(w_int), _ptr(workspace), _stream(stream)), "bcq_quant_gptq")
+
+
+def from_linear_rows(M, N, n_bits, q, class_of_plane, w_int, S, qbias, codes, alpha, offset, stream=None):
+    _check(lib().bcq_from_linear_rows(int(M), int(N), int(n_bits), int(q), _ptr(class_of_plane), _ptr(w_int), _ptr(S),
+                                      _ptr(qbias), _ptr(codes), _ptr(alpha), _ptr(offset), _stream(stream)),
+           "bcq_from_linear_rows")
 
 
 def unpack(desc, packed, codes, alpha, offset, stream=None):

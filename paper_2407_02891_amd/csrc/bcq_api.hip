@@ -109,6 +109,68 @@ bcq_status bcq_from_linear(int32_t M, int32_t N, int32_t group, int32_t n_bits, 
                : BCQ_ERR_HIP;
 }
 
+static bool quant_shape_ok(int32_t M, int32_t N, int32_t n_bits, int32_t q, bcq_status *why)
+{
+    *why = BCQ_ERR_INVALID_ARG;
+    if (M <= 0 || N <= 0 || n_bits < 2 || n_bits > 8 || q < 1 || q > n_bits) return false;
+    *why = BCQ_ERR_UNSUPPORTED;
+    if (q > kMaxQ || N > 65536) return false;
+    *why = BCQ_OK;
+    return true;
+}
+
+size_t bcq_quant_workspace_bytes(int32_t M, int32_t N)
+{
+    if (M <= 0 || N <= 0) return 0;
+    return quant_workspace_bytes(M, N);
+}
+
+bcq_status bcq_quant_search(int32_t M, int32_t N, int32_t n_bits, int32_t q, int32_t grid, const float *W,
+                            const float *H, float *S, float *qbias, int8_t *class_of_plane, float *err,
+                            void *workspace, void *stream)
+{
+    bcq_status why;
+    if (!quant_shape_ok(M, N, n_bits, q, &why)) return why;
+    if (grid < 1 || grid > 4096) return BCQ_ERR_INVALID_ARG;
+    if (!W || !H || !S || !qbias || !class_of_plane) return BCQ_ERR_INVALID_ARG;
+    if (!workspace || !aligned(workspace, 16)) return BCQ_ERR_WORKSPACE;
+    if (!aligned(W, 4) || !aligned(H, 4) || !aligned(S, 4) || !aligned(qbias, 4) || (err && !aligned(err, 4)))
+        return BCQ_ERR_INVALID_ARG;
+    return launch_quant_search(M, N, n_bits, q, grid, W, H, S, qbias, class_of_plane, err, workspace,
+                               static_cast<hipStream_t>(stream)) == hipSuccess
+               ? BCQ_OK
+               : BCQ_ERR_HIP;
+}
+
+bcq_status bcq_quant_gptq(int32_t M, int32_t N, int32_t n_bits, int32_t q, const float *W, const float *U,
+                          const float *S, const float *qbias, const int8_t *class_of_plane, uint8_t *w_int,
+                          void *workspace, void *stream)
+{
+    bcq_status why;
+    if (!quant_shape_ok(M, N, n_bits, q, &why)) return why;
+    if (!W || !U || !S || !qbias || !class_of_plane || !w_int) return BCQ_ERR_INVALID_ARG;
+    if (!workspace || !aligned(workspace, 16)) return BCQ_ERR_WORKSPACE;
+    if (!aligned(W, 4) || !aligned(U, 4) || !aligned(S, 4) || !aligned(qbias, 4)) return BCQ_ERR_INVALID_ARG;
+    return launch_quant_gptq(M, N, n_bits, q, W, U, S, qbias, class_of_plane, w_int, workspace,
+                             static_cast<hipStream_t>(stream)) == hipSuccess
+               ? BCQ_OK
+               : BCQ_ERR_HIP;
+}
+
+bcq_status bcq_from_linear_rows(int32_t M, int32_t N, int32_t n_bits, int32_t q, const int8_t *class_of_plane,
+                                const uint8_t *w_int, const float *S, const float *qbias, uint8_t *codes,
+                                uint16_t *alpha, uint16_t *offset, void *stream)
+{
+    bcq_status why;
+    if (!quant_shape_ok(M, N, n_bits, q, &why)) return why;
+    if (!class_of_plane || !w_int || !S || !qbias || !codes || !alpha || !offset) return BCQ_ERR_INVALID_ARG;
+    if (!aligned(S, 4) || !aligned(qbias, 4) || !aligned(alpha, 2) || !aligned(offset, 2)) return BCQ_ERR_INVALID_ARG;
+    return launch_from_linear_rows(M, N, n_bits, q, class_of_plane, w_int, S, qbias, codes, alpha, offset,
+                                   static_cast<hipStream_t>(stream)) == hipSuccess
+               ? BCQ_OK
+               : BCQ_ERR_HIP;
+}
+
 bcq_status bcq_unpack(const bcq_desc *desc, const void *packed, uint8_t *codes, uint16_t *alpha,
                       uint16_t *offset, void *stream)
 {

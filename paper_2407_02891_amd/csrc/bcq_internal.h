@@ -19,6 +19,16 @@ hipError_t launch_fill_zero(void *ptr, size_t bytes, hipStream_t stream);
 hipError_t launch_from_linear(int M, int N, int group, int n_bits, int q, const int32_t *class_of_plane,
                               const uint8_t *w_int, const float *S, const float *qbias, uint8_t *codes,
                               uint16_t *alpha, uint16_t *offset, hipStream_t stream);
+// The quantiser (row-wise parameters): search over scales and plane tyings, GPTQ pass, fusion.
+size_t quant_workspace_bytes(int M, int N);
+hipError_t launch_quant_search(int M, int N, int n_bits, int q, int grid, const float *W, const float *H, float *S,
+                               float *qbias, int8_t *labels, float *err_out, void *workspace, hipStream_t stream);
+hipError_t launch_quant_gptq(int M, int N, int n_bits, int q, const float *W, const float *U, const float *S,
+                             const float *qbias, const int8_t *labels, uint8_t *w_int, void *workspace,
+                             hipStream_t stream);
+hipError_t launch_from_linear_rows(int M, int N, int n_bits, int q, const int8_t *labels, const uint8_t *w_int,
+                                   const float *S, const float *qbias, uint8_t *codes, uint16_t *alpha,
+                                   uint16_t *offset, hipStream_t stream);
 struct ConvertPlan;
 bool make_convert_plan(int n_bits, int q, const int32_t *class_of_plane, ConvertPlan *plan);
 // Launch shape of the GEMV (bcq_set_option); zeros mean "choose automatically".

@@ -159,6 +159,43 @@ def test_from_linear_argument_checks():
     assert f(16, 256, 128, 3, 2, good, ok, ok + 2, ok, ok, ok, ok) == B.BCQ_ERR_INVALID_ARG  # S misaligned
 
 
+def test_quantizer_argument_checks():
+    L = bcq.lib()
+    ok = 0x1000
+    assert L.bcq_quant_workspace_bytes(0, 64) == 0
+    need = L.bcq_quant_workspace_bytes(70, 160)
+    assert need >= 4 * (70 * 160 + 70 * 3 + 3 * 70 + 128 * 70) and need % 256 == 0
+    search = lambda M, N, n, q, grid, *p: L.bcq_quant_search(M, N, n, q, grid, *(p or (ok,) * 7), None)
+    assert search(0, 64, 3, 2, 4) == B.BCQ_ERR_INVALID_ARG
+    assert search(8, 64, 1, 1, 4) == B.BCQ_ERR_INVALID_ARG              # Eq. 7 needs n >= 2
+    assert search(8, 64, 9, 2, 4) == B.BCQ_ERR_INVALID_ARG
+    assert search(8, 64, 3, 4, 4) == B.BCQ_ERR_INVALID_ARG              # more classes than planes
+    assert search(8, 64, 6, 5, 4) == B.BCQ_ERR_UNSUPPORTED
+    assert search(8, 1 << 17, 3, 2, 4) == B.BCQ_ERR_UNSUPPORTED
+    assert search(8, 64, 3, 2, 0) == B.BCQ_ERR_INVALID_ARG
+    for k in range(5):                                                  # W, H, S, qbias, labels
+        p = [ok] * 7
+        p[k] = None
+        assert search(8, 64, 3, 2, 4, *p) == B.BCQ_ERR_INVALID_ARG
+    assert search(8, 64, 3, 2, 4, ok, ok, ok, ok, ok, ok, None) == B.BCQ_ERR_WORKSPACE
+    assert search(8, 64, 3, 2, 4, ok, ok, ok, ok, ok, ok, ok + 4) == B.BCQ_ERR_WORKSPACE
+    assert search(8, 64, 3, 2, 4, ok + 2, ok, ok, ok, ok, ok, ok) == B.BCQ_ERR_INVALID_ARG
+    gptq = lambda M, N, n, q, *p: L.bcq_quant_gptq(M, N, n, q, *(p or (ok,) * 7), None)
+    assert gptq(8, 0, 3, 2) == B.BCQ_ERR_INVALID_ARG
+    for k in range(6):
+        p = [ok] * 7
+        p[k] = None
+        assert gptq(8, 64, 3, 2, *p) == B.BCQ_ERR_INVALID_ARG
+    assert gptq(8, 64, 3, 2, ok, ok, ok, ok, ok, ok, None) == B.BCQ_ERR_WORKSPACE
+    rows = lambda M, N, n, q, *p: L.bcq_from_linear_rows(M, N, n, q, *(p or (ok,) * 7), None)
+    assert rows(8, 64, 3, 0) == B.BCQ_ERR_INVALID_ARG
+    for k in range(7):
+        p = [ok] * 7
+        p[k] = None
+        assert rows(8, 64, 3, 2, *p) == B.BCQ_ERR_INVALID_ARG
+    assert rows(8, 64, 3, 2, ok, ok, ok, ok, ok, ok + 1, ok) == B.BCQ_ERR_INVALID_ARG   # alpha misaligned
+
+
 def test_misc_argument_checks():
     L = bcq.lib()
     assert L.bcq_workspace_init(None, 64, None) == B.BCQ_ERR_INVALID_ARG
