@@ -159,35 +159,57 @@ def test_from_linear_rows(M, N, n, q):
     U.gate(y[None, :], ref.gemm(planes, a16, z16, x), f"from_linear_rows n={n} q={q}")
 
 
-def test_quantise_then_multiply():
-    """The whole chain on one small layer: search, GPTQ pass, fusion, packing, product; the product
-    must reproduce the dequantised weights S W_q + qbias up to the binary16 scales."""
-    M, N, n, q = 48, 512, 3, 2
-    W32, H32 = _layer(M, N, seed=77)
-    S = torch.empty(M, dtype=torch.float32, device="cuda")
-    b = torch.empty(M, dtype=torch.float32, device="cuda")
-    lab = torch.empty((M, n), dtype=torch.int8, device="cuda")
-    ws = torch.empty(bcq.quant_workspace_bytes(M, N), dtype=torch.uint8, device="cuda")
-    W_dev = _dev(W32)
-    bcq.quant_search(M, N, n, q, 4, W_dev, _dev(H32), S, b, lab, None, ws)
+def test_many_column_blocks():
+    """A layer wide enough for 16 blocks of the GPTQ pass and 32 column tiles of the quadratic form;
+    the oracle runs on sampled rows (rows are independent in both steps)."""
+    M, N, n, q, grid = 300, 2048, 3, 2, 3
+    W32, H32 = _layer(M, N, seed=9)
+    rows = np.array([0, 63, 64, 255, 299])
+    S_g, b_g, lab_g, e_g = _gpu_search(W32, H32, n, q, grid)
+    S_o, b_o, p_o, e_o = quantizer.search(W32[rows], H32, n, q, grid)
+    parts = fuse.all_partitions(n, q)
+    assert np.array_equal(b_g[rows], b_o.astype(np.float32))
+    assert np.allclose(e_g[rows], e_o, rtol=1e-4, atol=0)
+    for k, m in enumerate(rows):
+        assert _partition_of(lab_g[m]) == parts[p_o[k]] and S_g[m] == np.float32(S_o[k]), m
     U32 = quantizer.cholesky_factor(H32).astype(np.float32)
     w_int = torch.empty((M, N), dtype=torch.uint8, device="cuda")
-    bcq.quant_gptq(M, N, n, q, W_dev, _dev(U32), S, b, lab, w_int, ws)
-    codes = torch.empty((M, N), dtype=torch.uint8, device="cuda")
-    alpha = torch.empty((M, 1, q), dtype=torch.float16, device="cuda")
-    off = torch.empty((M, 1), dtype=torch.float16, device="cuda")
-    bcq.from_linear_rows(M, N, n, q, lab, w_int, S, b, codes, alpha, off)
-    layer = bcq.PackedLayer(M, N, q, N, True)
-    layer.pack_from(codes, alpha, off)
+    ws = torch.empty(bcq.quant_workspace_bytes(M, N), dtype=torch.uint8, device="cuda")
+    bcq.quant_gptq(M, N, n, q, _dev(W32), _dev(U32), _dev(S_g), _dev(b_g), _dev(lab_g), w_int, ws)
+    torch.cuda.synchronize()
+    Wq_g = w_int.cpu().numpy().astype(np.int64)[rows]
+    choices = [fuse.bcchoice(parts[i], n) for i in p_o]
+    Sr, br = S_g[rows].astype(np.float64), b_g[rows].astype(np.float64)
+    Wq_o = quantizer.gptq(W32[rows], H32, Sr, br, choices, n)
+    assert float(np.mean(Wq_g != Wq_o)) <= 5e-3
+    e_gptq_o = quantizer.output_error(W32[rows], Wq_o, Sr, br, H32)
+    e_gptq_g = quantizer.output_error(W32[rows], Wq_g, Sr, br, H32)
+    assert np.allclose(e_gptq_g, e_gptq_o, rtol=2e-2), (e_gptq_g, e_gptq_o)
+
+
+def test_quantise_then_multiply():
+    """The whole chain on one small layer (quantize_layer: search, GPTQ pass, fusion, packing), then the
+    product; it must reproduce the dequantised weights S W_q + qbias up to the binary16 scales."""
+    from paper_2407_02891_amd.quantize import quantize_layer
+    M, N, n, q = 48, 512, 3, 2
+    W32, H32 = _layer(M, N, seed=77)
+    layer, info = quantize_layer(_dev(W32), _dev(H32), n, q, grid=4)
+    torch.cuda.synchronize()
+    S, b = info["S"].cpu().numpy().astype(np.float64), info["qbias"].cpu().numpy().astype(np.float64)
+    Wq = info["w_int"].cpu().numpy().astype(np.int64)
     rng = np.random.default_rng(5)
     x = rng.standard_normal((1, N)).astype(np.float16)
     y = U.gpu_gemv(layer, U.to_dev(x.view(np.uint16).astype(np.int16)).view(torch.float16))
-    W_hat = S.cpu().numpy().astype(np.float64)[:, None] * w_int.cpu().numpy() + b.cpu().numpy().astype(np.float64)[:, None]
-    y_lin = W_hat @ x[0].astype(np.float64)
+    y_lin = (S[:, None] * Wq + b[:, None]) @ x[0].astype(np.float64)
     rms = np.sqrt(np.mean(y_lin ** 2))
     assert np.abs(y.astype(np.float64) - y_lin).max() <= 4e-3 * max(rms, np.abs(y_lin).max())
-    # the quantised layer is a usable approximation of the original one on the calibration statistics
-    e = quantizer.output_error(W32, w_int.cpu().numpy().astype(np.int64), S.cpu().numpy().astype(np.float64),
-                               b.cpu().numpy().astype(np.float64), H32).sum()
+    # the result is what the oracle's chain gives from the same search result
+    parts = fuse.all_partitions(n, q)
+    choices = [fuse.bcchoice(_partition_of(l), n) for l in info["class_of_plane"].cpu().numpy()]
+    assert all(_partition_of(l) in parts for l in info["class_of_plane"].cpu().numpy())
+    Wq_o = quantizer.gptq(W32, H32, S, b, choices, n)
+    assert float(np.mean(Wq != Wq_o)) <= 5e-3
+    # and the quantised layer is a usable approximation of the original one on the calibration statistics
+    e = quantizer.output_error(W32, Wq, S, b, H32).sum()
     ref_energy = np.einsum("mk,kl,ml->", W32.astype(np.float64), H32.astype(np.float64) / 2, W32.astype(np.float64))
     assert e < 0.25 * ref_energy
