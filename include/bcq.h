@@ -145,16 +145,18 @@ bcq_status bcq_from_linear(int32_t M, int32_t N, int32_t group, int32_t n_bits, 
  *                      (use group = N and has_offset = 1 for bcq_pack).
  *
  *   W   DEVICE [M][N] binary32 weights (not modified)
- *   H   DEVICE [N][N] binary32, 2 X X^T of the calibration inputs (symmetric)
- *   U   DEVICE [N][N] binary32, upper triangular
+ *   H   DEVICE [N][N] binary32, 2 X X^T of the calibration inputs, 16-byte aligned
+ *   U   DEVICE [N][N] binary32, upper triangular, 16-byte aligned
  *   S, qbias DEVICE [M] binary32 (out of search, in of the others)
  *   class_of_plane DEVICE [M][n_bits] int8: class (0..q-1) of bit i of row m (out of search)
  *   err DEVICE [M] binary32 or NULL: the smallest error found (out)
  *   w_int DEVICE [M][N] uint8: integers in the row's representable set (out of gptq)
  *   codes DEVICE [M][N] uint8, alpha DEVICE [M][q] binary16, offset DEVICE [M] binary16 (out)
  *   workspace DEVICE, bcq_quant_workspace_bytes(M, N) bytes, 16-byte aligned (scratch, no init)
- * 2 <= n_bits <= 8, q <= n_bits, 1 <= grid <= 4096; q > 4 or N > 65536 is BCQ_ERR_UNSUPPORTED.
- * Integer decisions are taken in binary64; the error sums and the compensation run in binary32.
+ * N a multiple of 4, 2 <= n_bits <= 8, q <= n_bits, 1 <= grid <= 4096; q > 4 or N > 32768 is
+ * BCQ_ERR_UNSUPPORTED (all three calls).
+ * Integer decisions are taken in binary64; the error sums and the compensation run in binary32
+ * on the matrix cores (v_mfma_f32_32x32x2_f32).
  */
 size_t bcq_quant_workspace_bytes(int32_t M, int32_t N);
 bcq_status bcq_quant_search(int32_t M, int32_t N, int32_t n_bits, int32_t q, int32_t grid, const float *W,

@@ -112,9 +112,9 @@ bcq_status bcq_from_linear(int32_t M, int32_t N, int32_t group, int32_t n_bits, 
 static bool quant_shape_ok(int32_t M, int32_t N, int32_t n_bits, int32_t q, bcq_status *why)
 {
     *why = BCQ_ERR_INVALID_ARG;
-    if (M <= 0 || N <= 0 || n_bits < 2 || n_bits > 8 || q < 1 || q > n_bits) return false;
+    if (M <= 0 || N <= 0 || N % 4 != 0 || n_bits < 2 || n_bits > 8 || q < 1 || q > n_bits) return false;
     *why = BCQ_ERR_UNSUPPORTED;
-    if (q > kMaxQ || N > 65536) return false;
+    if (q > kMaxQ || N > 32768) return false;
     *why = BCQ_OK;
     return true;
 }
@@ -134,7 +134,7 @@ bcq_status bcq_quant_search(int32_t M, int32_t N, int32_t n_bits, int32_t q, int
     if (grid < 1 || grid > 4096) return BCQ_ERR_INVALID_ARG;
     if (!W || !H || !S || !qbias || !class_of_plane) return BCQ_ERR_INVALID_ARG;
     if (!workspace || !aligned(workspace, 16)) return BCQ_ERR_WORKSPACE;
-    if (!aligned(W, 4) || !aligned(H, 4) || !aligned(S, 4) || !aligned(qbias, 4) || (err && !aligned(err, 4)))
+    if (!aligned(W, 4) || !aligned(H, 16) || !aligned(S, 4) || !aligned(qbias, 4) || (err && !aligned(err, 4)))
         return BCQ_ERR_INVALID_ARG;
     return launch_quant_search(M, N, n_bits, q, grid, W, H, S, qbias, class_of_plane, err, workspace,
                                static_cast<hipStream_t>(stream)) == hipSuccess
@@ -150,7 +150,7 @@ bcq_status bcq_quant_gptq(int32_t M, int32_t N, int32_t n_bits, int32_t q, const
     if (!quant_shape_ok(M, N, n_bits, q, &why)) return why;
     if (!W || !U || !S || !qbias || !class_of_plane || !w_int) return BCQ_ERR_INVALID_ARG;
     if (!workspace || !aligned(workspace, 16)) return BCQ_ERR_WORKSPACE;
-    if (!aligned(W, 4) || !aligned(U, 4) || !aligned(S, 4) || !aligned(qbias, 4)) return BCQ_ERR_INVALID_ARG;
+    if (!aligned(W, 4) || !aligned(U, 16) || !aligned(S, 4) || !aligned(qbias, 4)) return BCQ_ERR_INVALID_ARG;
     return launch_quant_gptq(M, N, n_bits, q, W, U, S, qbias, class_of_plane, w_int, workspace,
                              static_cast<hipStream_t>(stream)) == hipSuccess
                ? BCQ_OK

@@ -94,29 +94,193 @@ __device__ __forceinline__ int quant_int(double w, double S, double qbias, int n
 }
 
 // ---------------------------------------------------------------------------------
+// working layout
+// ---------------------------------------------------------------------------------
+// Both steps work on transposed binary32 copies, [column k][row m] with the row index fastest and a
+// pitch Mp = M rounded up to 4: one thread per row then reads and writes coalesced, and both dense
+// products below take their operands "k-major" (a tile is 16 values of the summation index by 128
+// contiguous floats).  Workspace, in floats:
+//   Wt [N][Mp] | Dt [N][Mp] | part [ceil(N/128)][Mp] | wmin, wmax, best [3][Mp] | Err [128][Mp]
+struct QuantWorkspace {
+    int Mp, ntile;
+    float *Wt, *Dt, *part, *wmin, *wmax, *best, *Err;
+};
+
+static int pitch_of(int M) { return (M + 3) / 4 * 4; }
+
+static QuantWorkspace carve(void *workspace, int M, int N)
+{
+    QuantWorkspace w;
+    w.Mp = pitch_of(M);
+    w.ntile = (N + 127) / 128;
+    w.Wt = static_cast<float *>(workspace);
+    w.Dt = w.Wt + (size_t)N * w.Mp;
+    w.part = w.Dt + (size_t)N * w.Mp;
+    w.wmin = w.part + (size_t)w.ntile * w.Mp;
+    w.wmax = w.wmin + w.Mp;
+    w.best = w.wmax + w.Mp;
+    w.Err = w.best + w.Mp;
+    return w;
+}
+
+size_t quant_workspace_bytes(int M, int N)
+{
+    const size_t Mp = pitch_of(M), ntile = (size_t)(N + 127) / 128;
+    const size_t floats = 2 * (size_t)N * Mp + ntile * Mp + 3 * Mp + 128 * Mp;
+    return (floats * 4 + 255) / 256 * 256;
+}
+
+// Wt[k][m] = W[m][k]; the pad rows m in [M, Mp) are written as zeros.
+__global__ void transpose_kernel(int M, int Mp, int N, const float *__restrict__ W, float *__restrict__ Wt)
+{
+    __shared__ float tile[32][33];
+    const int m0 = blockIdx.y * 32, k0 = blockIdx.x * 32;
+    for (int i = threadIdx.y; i < 32; i += blockDim.y) {
+        const int m = m0 + i, k = k0 + threadIdx.x;
+        tile[i][threadIdx.x] = (m < M && k < N) ? W[(size_t)m * N + k] : 0.0f;
+    }
+    __syncthreads();
+    for (int i = threadIdx.y; i < 32; i += blockDim.y) {
+        const int k = k0 + i, m = m0 + threadIdx.x;
+        if (m < Mp && k < N) Wt[(size_t)k * Mp + m] = tile[threadIdx.x][i];
+    }
+}
+
+// ---------------------------------------------------------------------------------
+// dense product on the matrix cores, binary32:  C[r][c] = sum_k A[k][r] * B[k][c]
+// ---------------------------------------------------------------------------------
+// A is [K][R] with pitch lda, B is [K][C] with pitch ldb (both pitches and R, C multiples of 4, all
+// pointers 16-byte aligned).  A workgroup of four waves owns a 128 x 128 tile of C, a wave a 64 x 64
+// quarter as 2 x 2 v_mfma_f32_32x32x2_f32 accumulators; the operand tiles (16 k x 128) go through
+// LDS, double-buffered, the next pair of tiles travelling through registers while the current one
+// is multiplied.  What happens to the finished tile is the caller's epilogue:
+//   kQuadForm   part[tile row][c] = sum over the tile's rows r of C[r][c] * E[r][c]   (E pitch ldb)
+//   kSubtract   Out[r][c] -= C[r][c]                                                  (Out pitch ldb)
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4v __attribute__((ext_vector_type(4)));
+enum { kQuadForm = 0, kSubtract = 1 };
+constexpr int kTile = 128, kStep = 16;
+
+__device__ __forceinline__ f32x4v load4_or_zero(const float *base, size_t pitch, int k, int K, int x, int X)
+{
+    if (k < K && x < X) return *reinterpret_cast<const f32x4v *>(base + (size_t)k * pitch + x);
+    return f32x4v{0.f, 0.f, 0.f, 0.f};
+}
+
+template <int MODE>
+__global__ __launch_bounds__(256) void mfma_kmajor_kernel(const float *__restrict__ A, int lda, int R,
+                                                          const float *__restrict__ B, int ldb, int C, int K,
+                                                          float *__restrict__ out, const float *__restrict__ E)
+{
+    __shared__ __attribute__((aligned(16))) float As[2][kStep][kTile];
+    __shared__ __attribute__((aligned(16))) float Bs[2][kStep][kTile];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int lo = lane & 31, hi = lane >> 5;
+    const int wr = wave >> 1, wc = wave & 1;
+    const int r0 = blockIdx.y * kTile, c0 = blockIdx.x * kTile;
+    // loader: thread t brings rows t/32 and t/32 + 8 of a 16 x 128 tile, four floats at column 4 (t%32)
+    const int lk = tid >> 5, lx = (tid & 31) * 4;
+
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.0f;
+
+    f32x4v ra[2], rb[2];
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        ra[h] = load4_or_zero(A, lda, lk + 8 * h, K, r0 + lx, R);
+        rb[h] = load4_or_zero(B, ldb, lk + 8 * h, K, c0 + lx, C);
+    }
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        *reinterpret_cast<f32x4v *>(&As[0][lk + 8 * h][lx]) = ra[h];
+        *reinterpret_cast<f32x4v *>(&Bs[0][lk + 8 * h][lx]) = rb[h];
+    }
+    __syncthreads();
+    int buf = 0;
+    for (int k0 = 0; k0 < K; k0 += kStep) {
+        const bool more = k0 + kStep < K;
+        if (more) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                ra[h] = load4_or_zero(A, lda, k0 + kStep + lk + 8 * h, K, r0 + lx, R);
+                rb[h] = load4_or_zero(B, ldb, k0 + kStep + lk + 8 * h, K, c0 + lx, C);
+            }
+        }
+#pragma unroll
+        for (int s = 0; s < kStep / 2; ++s) {
+            const float a0 = As[buf][2 * s + hi][wr * 64 + lo], a1 = As[buf][2 * s + hi][wr * 64 + 32 + lo];
+            const float b0 = Bs[buf][2 * s + hi][wc * 64 + lo], b1 = Bs[buf][2 * s + hi][wc * 64 + 32 + lo];
+            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
+            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
+            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
+            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+        }
+        if (more) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                *reinterpret_cast<f32x4v *>(&As[buf ^ 1][lk + 8 * h][lx]) = ra[h];
+                *reinterpret_cast<f32x4v *>(&Bs[buf ^ 1][lk + 8 * h][lx]) = rb[h];
+            }
+        }
+        __syncthreads();  // the other buffer is complete, and everyone is done reading this one
+        buf ^= 1;
+    }
+
+    // element i of a 32 x 32 accumulator: row 8 (i/4) + 4 hi + i%4, column lo
+    if constexpr (MODE == kSubtract) {
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+            for (int b = 0; b < 2; ++b) {
+                const int c = c0 + wc * 64 + b * 32 + lo;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int r = r0 + wr * 64 + a * 32 + 8 * (i >> 2) + 4 * hi + (i & 3);
+                    if (r < R && c < C) out[(size_t)r * ldb + c] -= acc[a][b][i];
+                }
+            }
+    } else {
+        float *red = &As[0][0][0];  // [2 row halves][128 columns], free after the loop's last barrier
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+            const int c = c0 + wc * 64 + b * 32 + lo;
+            float sum = 0.0f;
+#pragma unroll
+            for (int a = 0; a < 2; ++a)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int r = r0 + wr * 64 + a * 32 + 8 * (i >> 2) + 4 * hi + (i & 3);
+                    if (r < R && c < C) sum = fmaf(acc[a][b][i], E[(size_t)r * ldb + c], sum);
+                }
+            sum += __shfl_xor(sum, 32);
+            if (hi == 0) red[wr * kTile + wc * 64 + b * 32 + lo] = sum;
+        }
+        __syncthreads();
+        if (tid < kTile && c0 + tid < C) out[(size_t)blockIdx.y * ldb + c0 + tid] = red[tid] + red[kTile + tid];
+    }
+}
+
+// ---------------------------------------------------------------------------------
 // search
 // ---------------------------------------------------------------------------------
-__global__ void row_range_kernel(int M, int N, const float *__restrict__ W, float *__restrict__ wmin,
+__global__ void row_range_kernel(int M, int Mp, int N, const float *__restrict__ Wt, float *__restrict__ wmin,
                                  float *__restrict__ wmax)
 {
-    const int m = blockIdx.x;
+    const int m = blockIdx.x * blockDim.x + threadIdx.x;
+    if (m >= M) return;
     float lo = INFINITY, hi = -INFINITY;
-    for (int k = threadIdx.x; k < N; k += blockDim.x) {
-        const float v = W[(size_t)m * N + k];
+    for (int k = 0; k < N; ++k) {
+        const float v = Wt[(size_t)k * Mp + m];
         lo = fminf(lo, v);
         hi = fmaxf(hi, v);
     }
-    __shared__ float slo[256], shi[256];
-    slo[threadIdx.x] = lo; shi[threadIdx.x] = hi;
-    __syncthreads();
-    for (int s = 128; s > 0; s >>= 1) {
-        if ((int)threadIdx.x < s) {
-            slo[threadIdx.x] = fminf(slo[threadIdx.x], slo[threadIdx.x + s]);
-            shi[threadIdx.x] = fmaxf(shi[threadIdx.x], shi[threadIdx.x + s]);
-        }
-        __syncthreads();
-    }
-    if (threadIdx.x == 0) { wmin[m] = slo[0]; wmax[m] = shi[0]; }
+    wmin[m] = lo;
+    wmax[m] = hi;
 }
 
 // Scale of grid point g (0-based) of a row, Eq. 7, in binary64.
@@ -127,79 +291,27 @@ __device__ __forceinline__ double grid_scale(double wmin, double wmax, int n_bit
     return lo + (hi - lo) * ((double)(g + 1) / ((double)grid + 1.0));
 }
 
-// D[m][k] = S' W_q + qbias - w for one candidate (grid point g, tying t).
-__global__ void delta_kernel(int M, int N, int n_bits, int g, int grid, Tying t, const float *__restrict__ W,
-                             const float *__restrict__ wmin, const float *__restrict__ wmax, float *__restrict__ D)
+// Dt[k][m] = S' W_q + qbias - w for one candidate (grid point g, tying t); zeros in the pad rows.
+__global__ void delta_kernel(int M, int Mp, int N, int n_bits, int g, int grid, Tying t,
+                             const float *__restrict__ Wt, const float *__restrict__ wmin,
+                             const float *__restrict__ wmax, float *__restrict__ Dt)
 {
-    const size_t gid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (gid >= (size_t)M * N) return;
-    const int m = (int)(gid / N);
-    const double lo = wmin[m], S = grid_scale(lo, wmax[m], n_bits, g, grid);
-    const double w = W[gid];
-    const int wq = quant_int(w, S, lo, n_bits, t.choice, t.nchoice);
-    D[gid] = (float)(S * wq + lo - w);
+    const int m = blockIdx.x * blockDim.x + threadIdx.x;
+    const int k = blockIdx.y;
+    if (m >= Mp) return;
+    float d = 0.0f;
+    if (m < M) {
+        const double lo = wmin[m], S = grid_scale(lo, wmax[m], n_bits, g, grid);
+        const double w = Wt[(size_t)k * Mp + m];
+        const int wq = quant_int(w, S, lo, n_bits, t.choice, t.nchoice);
+        d = (float)(S * wq + lo - w);
+    }
+    Dt[(size_t)k * Mp + m] = d;
 }
 
-// part[m][tile] = sum over the 64 columns l of the tile of D[m][l] * (sum_k D[m][k] H[k][l]).
-constexpr int kBM = 64, kBN = 64, kBK = 16;
-__global__ __launch_bounds__(256) void quad_form_kernel(int M, int N, const float *__restrict__ D,
-                                                        const float *__restrict__ H, float *__restrict__ part,
-                                                        int ntile)
-{
-    __shared__ float As[kBK][kBM + 1];
-    __shared__ float Bs[kBK][kBN];
-    __shared__ float red[kBM][17];
-    const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
-    const int l0 = blockIdx.x * kBN, m0 = blockIdx.y * kBM;
-    float acc[4][4] = {};
-    for (int k0 = 0; k0 < N; k0 += kBK) {
-        for (int e = tid; e < kBM * kBK; e += 256) {  // D tile, 64 rows x 16 k
-            const int mm = e / kBK, kk = e % kBK;
-            const int m = m0 + mm, k = k0 + kk;
-            As[kk][mm] = (m < M && k < N) ? D[(size_t)m * N + k] : 0.0f;
-        }
-        for (int e = tid; e < kBK * kBN; e += 256) {  // H tile, 16 k x 64 l
-            const int kk = e / kBN, ll = e % kBN;
-            const int k = k0 + kk, l = l0 + ll;
-            Bs[kk][ll] = (k < N && l < N) ? H[(size_t)k * N + l] : 0.0f;
-        }
-        __syncthreads();
-#pragma unroll
-        for (int kk = 0; kk < kBK; ++kk) {
-            float a[4], b[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) a[i] = As[kk][ty * 4 + i];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) b[j] = Bs[kk][tx * 4 + j];
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
-        }
-        __syncthreads();
-    }
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int m = m0 + ty * 4 + i;
-        float s = 0.0f;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int l = l0 + tx * 4 + j;
-            if (m < M && l < N) s = fmaf(acc[i][j], D[(size_t)m * N + l], s);
-        }
-        red[ty * 4 + i][tx] = s;
-    }
-    __syncthreads();
-    if (tid < kBM) {  // fixed order: the result does not depend on timing
-        float s = 0.0f;
-        for (int t = 0; t < 16; ++t) s += red[tid][t];
-        const int m = m0 + tid;
-        if (m < M) part[(size_t)m * ntile + blockIdx.x] = s;
-    }
-}
-
-// err = (sum of the row's tile partials) / 2 (H = 2 X X^T); keep the candidate if it is strictly better.
-__global__ void keep_best_kernel(int M, int n_bits, int ntile, int g, int grid, int first, Tying t,
+// err = (sum of the row's tile partials, in tile order) / 2 (H = 2 X X^T); keep the candidate if it
+// is strictly better.
+__global__ void keep_best_kernel(int M, int Mp, int n_bits, int ntile, int g, int grid, int first, Tying t,
                                  const float *__restrict__ part, const float *__restrict__ wmin,
                                  const float *__restrict__ wmax, float *__restrict__ best, float *__restrict__ S,
                                  float *__restrict__ qbias, int8_t *__restrict__ labels)
@@ -207,7 +319,7 @@ __global__ void keep_best_kernel(int M, int n_bits, int ntile, int g, int grid, 
     const int m = blockIdx.x * blockDim.x + threadIdx.x;
     if (m >= M) return;
     float e = 0.0f;
-    for (int k = 0; k < ntile; ++k) e += part[(size_t)m * ntile + k];
+    for (int k = 0; k < ntile; ++k) e += part[(size_t)k * Mp + m];
     e *= 0.5f;
     if (first || e < best[m]) {
         best[m] = e;
@@ -217,39 +329,29 @@ __global__ void keep_best_kernel(int M, int n_bits, int ntile, int g, int grid, 
     }
 }
 
-size_t quant_workspace_bytes(int M, int N)
-{
-    const size_t ntile = (size_t)(N + kBN - 1) / kBN;
-    size_t floats = (size_t)M * N          // D, later the transposed working copy of W
-                    + (size_t)M * ntile    // tile partials
-                    + 3 * (size_t)M        // row min, row max, best error
-                    + 128 * (size_t)M;     // GPTQ: errors of one block of columns
-    return (floats * 4 + 255) / 256 * 256;
-}
-
 hipError_t launch_quant_search(int M, int N, int n_bits, int q, int grid, const float *W, const float *H, float *S,
                                float *qbias, int8_t *labels, float *err_out, void *workspace, hipStream_t stream)
 {
-    const int ntile = (N + kBN - 1) / kBN;
-    float *D = static_cast<float *>(workspace);
-    float *part = D + (size_t)M * N;
-    float *wmin = part + (size_t)M * ntile, *wmax = wmin + M, *best = wmax + M;
-    hipLaunchKernelGGL(row_range_kernel, dim3(M), dim3(256), 0, stream, M, N, W, wmin, wmax);
+    const QuantWorkspace w = carve(workspace, M, N);
+    hipLaunchKernelGGL(transpose_kernel, dim3((N + 31) / 32, (w.Mp + 31) / 32), dim3(32, 8), 0, stream, M, w.Mp, N, W,
+                       w.Wt);
+    hipLaunchKernelGGL(row_range_kernel, dim3((M + 63) / 64), dim3(64), 0, stream, M, w.Mp, N, w.Wt, w.wmin, w.wmax);
     const std::vector<Tying> tyings = all_tyings(n_bits, q);
-    const size_t total = (size_t)M * N;
     bool first = true;
     for (int g = 0; g < grid; ++g)
         for (const Tying &t : tyings) {
-            hipLaunchKernelGGL(delta_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, M, N, n_bits,
-                               g, grid, t, W, wmin, wmax, D);
-            hipLaunchKernelGGL(quad_form_kernel, dim3(ntile, (M + kBM - 1) / kBM), dim3(256), 0, stream, M, N, D, H,
-                               part, ntile);
-            hipLaunchKernelGGL(keep_best_kernel, dim3((M + 255) / 256), dim3(256), 0, stream, M, n_bits, ntile, g, grid,
-                               first ? 1 : 0, t, part, wmin, wmax, best, S, qbias, labels);
+            hipLaunchKernelGGL(delta_kernel, dim3((w.Mp + 255) / 256, N), dim3(256), 0, stream, M, w.Mp, N, n_bits, g,
+                               grid, t, w.Wt, w.wmin, w.wmax, w.Dt);
+            // C[l][m] = sum_k H[k][l] Dt[k][m]  (= (d H)[m][l] whether or not H is exactly symmetric:
+            // d H d^T = d H^T d^T), then the dot with Dt[l][m] over each tile's 128 values of l
+            hipLaunchKernelGGL((mfma_kmajor_kernel<kQuadForm>), dim3((w.Mp + kTile - 1) / kTile, w.ntile), dim3(256), 0,
+                               stream, H, N, N, w.Dt, w.Mp, w.Mp, N, w.part, w.Dt);
+            hipLaunchKernelGGL(keep_best_kernel, dim3((M + 255) / 256), dim3(256), 0, stream, M, w.Mp, n_bits, w.ntile, g,
+                               grid, first ? 1 : 0, t, w.part, w.wmin, w.wmax, w.best, S, qbias, labels);
             first = false;
         }
     if (err_out) {
-        hipError_t e = hipMemcpyAsync(err_out, best, (size_t)M * 4, hipMemcpyDeviceToDevice, stream);
+        hipError_t e = hipMemcpyAsync(err_out, w.best, (size_t)M * 4, hipMemcpyDeviceToDevice, stream);
         if (e != hipSuccess) return e;
     }
     return hipGetLastError();
@@ -283,24 +385,9 @@ __device__ __forceinline__ void row_choice(const int8_t *label, int n_bits, int 
     }
 }
 
-__global__ void transpose_kernel(int M, int N, const float *__restrict__ W, float *__restrict__ Wt)
-{
-    __shared__ float tile[32][33];
-    const int m0 = blockIdx.y * 32, k0 = blockIdx.x * 32;
-    for (int i = threadIdx.y; i < 32; i += blockDim.y) {
-        const int m = m0 + i, k = k0 + threadIdx.x;
-        tile[i][threadIdx.x] = (m < M && k < N) ? W[(size_t)m * N + k] : 0.0f;
-    }
-    __syncthreads();
-    for (int i = threadIdx.y; i < 32; i += blockDim.y) {
-        const int k = k0 + i, m = m0 + threadIdx.x;
-        if (m < M && k < N) Wt[(size_t)k * M + m] = tile[threadIdx.x][i];
-    }
-}
-
 // One block of up to 128 columns [c0, c1): one thread per row, the block's columns of the row in LDS.
 constexpr int kGptqBlock = 128, kGptqRows = 64;
-__global__ __launch_bounds__(kGptqRows) void gptq_block_kernel(int M, int N, int n_bits, int q, int c0, int c1,
+__global__ __launch_bounds__(kGptqRows) void gptq_block_kernel(int M, int Mp, int N, int n_bits, int q, int c0, int c1,
                                                                float *__restrict__ Wt, const float *__restrict__ U,
                                                                const float *__restrict__ S, const float *__restrict__ qbias,
                                                                const int8_t *__restrict__ labels,
@@ -316,7 +403,7 @@ __global__ __launch_bounds__(kGptqRows) void gptq_block_kernel(int M, int N, int
         row_choice(labels + (size_t)m * n_bits, n_bits, q, choice);
         s = S[m]; b = qbias[m];
     }
-    for (int j = 0; j < cols; ++j) wl[j][tm] = live ? Wt[(size_t)(c0 + j) * M + m] : 0.0f;
+    for (int j = 0; j < cols; ++j) wl[j][tm] = live ? Wt[(size_t)(c0 + j) * Mp + m] : 0.0f;
     for (int j = 0; j < cols; ++j) {
         const int c = c0 + j;
         const float w = wl[j][tm];
@@ -327,38 +414,26 @@ __global__ __launch_bounds__(kGptqRows) void gptq_block_kernel(int M, int N, int
             const float qv = (float)(s * wq + b);
             e = (w - qv) / U[(size_t)c * N + c];
         }
-        if (live) Err[(size_t)j * M + m] = e;
+        if (m < Mp) Err[(size_t)j * Mp + m] = e;  // zeros in the pad rows
         for (int k = j + 1; k < cols; ++k) wl[k][tm] = fmaf(-e, U[(size_t)c * N + c0 + k], wl[k][tm]);
     }
-}
-
-// Wt[k][m] -= sum_j Err[j][m] U[c0 + j][k] for the columns k >= c1.
-__global__ void gptq_trailing_kernel(int M, int N, int c0, int c1, float *__restrict__ Wt, const float *__restrict__ U,
-                                     const float *__restrict__ Err)
-{
-    const int m = blockIdx.x * blockDim.x + threadIdx.x;
-    const int k = c1 + blockIdx.y;
-    if (m >= M || k >= N) return;
-    float acc = 0.0f;
-    for (int j = 0; j < c1 - c0; ++j) acc = fmaf(Err[(size_t)j * M + m], U[(size_t)(c0 + j) * N + k], acc);
-    Wt[(size_t)k * M + m] -= acc;
 }
 
 hipError_t launch_quant_gptq(int M, int N, int n_bits, int q, const float *W, const float *U, const float *S,
                              const float *qbias, const int8_t *labels, uint8_t *w_int, void *workspace,
                              hipStream_t stream)
 {
-    const int ntile = (N + kBN - 1) / kBN;
-    float *Wt = static_cast<float *>(workspace);
-    float *Err = Wt + (size_t)M * N + (size_t)M * ntile + 3 * (size_t)M;
-    hipLaunchKernelGGL(transpose_kernel, dim3((N + 31) / 32, (M + 31) / 32), dim3(32, 8), 0, stream, M, N, W, Wt);
+    const QuantWorkspace w = carve(workspace, M, N);
+    hipLaunchKernelGGL(transpose_kernel, dim3((N + 31) / 32, (w.Mp + 31) / 32), dim3(32, 8), 0, stream, M, w.Mp, N, W,
+                       w.Wt);
     for (int c0 = 0; c0 < N; c0 += kGptqBlock) {
         const int c1 = c0 + kGptqBlock < N ? c0 + kGptqBlock : N;
-        hipLaunchKernelGGL(gptq_block_kernel, dim3((M + kGptqRows - 1) / kGptqRows), dim3(kGptqRows), 0, stream, M, N,
-                           n_bits, q, c0, c1, Wt, U, S, qbias, labels, w_int, Err);
-        if (c1 < N)
-            hipLaunchKernelGGL(gptq_trailing_kernel, dim3((M + 255) / 256, N - c1), dim3(256), 0, stream, M, N, c0, c1,
-                               Wt, U, Err);
+        hipLaunchKernelGGL(gptq_block_kernel, dim3((w.Mp + kGptqRows - 1) / kGptqRows), dim3(kGptqRows), 0, stream, M,
+                           w.Mp, N, n_bits, q, c0, c1, w.Wt, U, S, qbias, labels, w_int, w.Err);
+        if (c1 < N)  // Wt[k][m] -= sum_j U[c0 + j][k] Err[j][m] for the columns k >= c1
+            hipLaunchKernelGGL((mfma_kmajor_kernel<kSubtract>), dim3((w.Mp + kTile - 1) / kTile, (N - c1 + kTile - 1) / kTile),
+                               dim3(256), 0, stream, U + (size_t)c0 * N + c1, N, N - c1, w.Err, w.Mp, w.Mp, c1 - c0,
+                               w.Wt + (size_t)c1 * w.Mp, nullptr);
     }
     return hipGetLastError();
 }

@@ -164,7 +164,7 @@ def test_quantizer_argument_checks():
     ok = 0x1000
     assert L.bcq_quant_workspace_bytes(0, 64) == 0
     need = L.bcq_quant_workspace_bytes(70, 160)
-    assert need >= 4 * (70 * 160 + 70 * 3 + 3 * 70 + 128 * 70) and need % 256 == 0
+    assert need >= 4 * (2 * 160 * 72 + 2 * 72 + 3 * 72 + 128 * 72) and need % 256 == 0   # row pitch 72
     search = lambda M, N, n, q, grid, *p: L.bcq_quant_search(M, N, n, q, grid, *(p or (ok,) * 7), None)
     assert search(0, 64, 3, 2, 4) == B.BCQ_ERR_INVALID_ARG
     assert search(8, 64, 1, 1, 4) == B.BCQ_ERR_INVALID_ARG              # Eq. 7 needs n >= 2
@@ -172,6 +172,7 @@ def test_quantizer_argument_checks():
     assert search(8, 64, 3, 4, 4) == B.BCQ_ERR_INVALID_ARG              # more classes than planes
     assert search(8, 64, 6, 5, 4) == B.BCQ_ERR_UNSUPPORTED
     assert search(8, 1 << 17, 3, 2, 4) == B.BCQ_ERR_UNSUPPORTED
+    assert search(8, 66, 3, 2, 4) == B.BCQ_ERR_INVALID_ARG              # N not a multiple of 4
     assert search(8, 64, 3, 2, 0) == B.BCQ_ERR_INVALID_ARG
     for k in range(5):                                                  # W, H, S, qbias, labels
         p = [ok] * 7
@@ -180,6 +181,7 @@ def test_quantizer_argument_checks():
     assert search(8, 64, 3, 2, 4, ok, ok, ok, ok, ok, ok, None) == B.BCQ_ERR_WORKSPACE
     assert search(8, 64, 3, 2, 4, ok, ok, ok, ok, ok, ok, ok + 4) == B.BCQ_ERR_WORKSPACE
     assert search(8, 64, 3, 2, 4, ok + 2, ok, ok, ok, ok, ok, ok) == B.BCQ_ERR_INVALID_ARG
+    assert search(8, 64, 3, 2, 4, ok, ok + 8, ok, ok, ok, ok, ok) == B.BCQ_ERR_INVALID_ARG   # H: 16 bytes
     gptq = lambda M, N, n, q, *p: L.bcq_quant_gptq(M, N, n, q, *(p or (ok,) * 7), None)
     assert gptq(8, 0, 3, 2) == B.BCQ_ERR_INVALID_ARG
     for k in range(6):
