@@ -268,16 +268,34 @@ __global__ __launch_bounds__(256) void mfma_kmajor_kernel(const float *__restric
 // ---------------------------------------------------------------------------------
 // search
 // ---------------------------------------------------------------------------------
-__global__ void row_range_kernel(int M, int Mp, int N, const float *__restrict__ Wt, float *__restrict__ wmin,
-                                 float *__restrict__ wmax)
+// Row minimum and maximum in two steps: `chunks` slabs of columns each leave a partial pair in
+// scratch ([chunks][Mp] minima, then [chunks][Mp] maxima), a second launch combines them.
+__global__ void row_range_partial_kernel(int M, int Mp, int N, int chunks, const float *__restrict__ Wt,
+                                         float *__restrict__ scratch)
+{
+    const int m = blockIdx.x * blockDim.x + threadIdx.x, chunk = blockIdx.y;
+    if (m >= M) return;
+    const int per = (N + chunks - 1) / chunks;
+    const int k_end = (chunk + 1) * per < N ? (chunk + 1) * per : N;
+    float lo = INFINITY, hi = -INFINITY;
+    for (int k = chunk * per; k < k_end; ++k) {
+        const float v = Wt[(size_t)k * Mp + m];
+        lo = fminf(lo, v);
+        hi = fmaxf(hi, v);
+    }
+    scratch[(size_t)chunk * Mp + m] = lo;
+    scratch[(size_t)(chunks + chunk) * Mp + m] = hi;
+}
+
+__global__ void row_range_final_kernel(int M, int Mp, int chunks, const float *__restrict__ scratch,
+                                       float *__restrict__ wmin, float *__restrict__ wmax)
 {
     const int m = blockIdx.x * blockDim.x + threadIdx.x;
     if (m >= M) return;
     float lo = INFINITY, hi = -INFINITY;
-    for (int k = 0; k < N; ++k) {
-        const float v = Wt[(size_t)k * Mp + m];
-        lo = fminf(lo, v);
-        hi = fmaxf(hi, v);
+    for (int c = 0; c < chunks; ++c) {
+        lo = fminf(lo, scratch[(size_t)c * Mp + m]);
+        hi = fmaxf(hi, scratch[(size_t)(chunks + c) * Mp + m]);
     }
     wmin[m] = lo;
     wmax[m] = hi;
@@ -335,7 +353,11 @@ hipError_t launch_quant_search(int M, int N, int n_bits, int q, int grid, const 
     const QuantWorkspace w = carve(workspace, M, N);
     hipLaunchKernelGGL(transpose_kernel, dim3((N + 31) / 32, (w.Mp + 31) / 32), dim3(32, 8), 0, stream, M, w.Mp, N, W,
                        w.Wt);
-    hipLaunchKernelGGL(row_range_kernel, dim3((M + 63) / 64), dim3(64), 0, stream, M, w.Mp, N, w.Wt, w.wmin, w.wmax);
+    const int chunks = N / 2 < 64 ? N / 2 : 64;  // Dt (N rows, not yet in use) holds the 2 * chunks partial rows
+    hipLaunchKernelGGL(row_range_partial_kernel, dim3((M + 63) / 64, chunks), dim3(64), 0, stream, M, w.Mp, N, chunks,
+                       w.Wt, w.Dt);
+    hipLaunchKernelGGL(row_range_final_kernel, dim3((M + 63) / 64), dim3(64), 0, stream, M, w.Mp, chunks, w.Dt, w.wmin,
+                       w.wmax);
     const std::vector<Tying> tyings = all_tyings(n_bits, q);
     bool first = true;
     for (int g = 0; g < grid; ++g)
