@@ -6,8 +6,8 @@ batch 1 -- 7168x7168 (attention projection), 28672x7168 (fc1), 7168x28672 (fc2),
 q = 3, group 128, no offset, synthetic seeded inputs (bcq_synth).  One "step" is
 one pass over the layers, one bcq_gemv each, on one stream.  Weights are
 resident in HBM before timing; every step reads a different copy of the packed
-weights (the copies total > 1 GiB) so that neither L2 nor the 256 MB memory-side
-cache serves them.
+weights (the copies of the largest layer alone total at least 1 GiB) so that
+neither L2 nor the 256 MB memory-side cache serves them.
 
 Other workloads (--workload): `llama70b_block` = the seven GEMVs of a
 Llama-2-70B-shaped decoder block in sequence; `llama70b_block_fused` = the same
@@ -124,7 +124,8 @@ def main():
         y = torch.empty((B, M), dtype=torch.float16, device=dev)
         layers[name] = dict(subs=subs, pl=pl, x=x, y=y, bytes=nbytes, copies=[pl.packed])
         total_bytes += nbytes
-    n_copies = max(2, math.ceil(1.25 * 2 ** 30 / total_bytes))
+    # enough copies that the largest layer alone rotates over at least 1 GiB (13 for 86.7 MB)
+    n_copies = max(2, math.ceil(2 ** 30 / max(ent["bytes"] for ent in layers.values())))
     for name in layers:
         ent = layers[name]
         ent["copies"] += [ent["pl"].packed.clone() for _ in range(n_copies - 1)]
