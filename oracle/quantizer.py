@@ -10,7 +10,8 @@ Readings where the paper is silent (also listed in the design notes):
   * quantisation parameters are per row (Sec. II-A: "row-wisely"); the grid search of Eq. 7 and
     the choice of the tied-plane set are done per row, keeping the row's best pair;
   * qbias = W_min of the row; the first-step scale is (W_max - W_min) / (2^n - 1); Eq. 7's open
-    interval is searched on `grid` equidistant interior points, ascending;
+    interval is searched on `grid` equidistant interior points, ascending; for a constant row
+    (W_max = W_min, Eq. 7's interval is empty) the scale is 1 and every integer is 0;
   * the search criterion of Eq. 5 ("argmin (W_q X)") is the output error of the row,
     ||(w_hat - w) X||^2 = (w_hat - w) (X X^T) (w_hat - w)^T, with w_hat = S' W_q + qbias and
     W_q = nearest-BCchoice(linear-quant(w)) -- no error compensation inside the search;
@@ -33,6 +34,8 @@ def hessian(X):
 
 def scale_grid(w_min, w_max, n, grid):
     """Eq. 7: `grid` equidistant points strictly inside ((Wmax-Wmin)/(2^(n+1)-1), (Wmax-Wmin)/(2^(n-1)-1))."""
+    if w_max == w_min:                                  # a constant row: every scale reproduces it (W_int = 0)
+        return np.ones(grid)
     lo = (w_max - w_min) / (2 ** (n + 1) - 1)
     hi = (w_max - w_min) / (2 ** (n - 1) - 1)
     return lo + (hi - lo) * (np.arange(1, grid + 1) / (grid + 1.0))

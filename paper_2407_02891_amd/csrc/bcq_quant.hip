@@ -304,6 +304,7 @@ __global__ void row_range_final_kernel(int M, int Mp, int chunks, const float *_
 // Scale of grid point g (0-based) of a row, Eq. 7, in binary64.
 __device__ __forceinline__ double grid_scale(double wmin, double wmax, int n_bits, int g, int grid)
 {
+    if (wmax == wmin) return 1.0;  // a constant row: Eq. 7's interval is empty, any scale reproduces it
     const double lo = (wmax - wmin) / (double)((1 << (n_bits + 1)) - 1);
     const double hi = (wmax - wmin) / (double)((1 << (n_bits - 1)) - 1);
     return lo + (hi - lo) * ((double)(g + 1) / ((double)grid + 1.0));

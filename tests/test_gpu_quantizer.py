@@ -159,6 +159,34 @@ def test_from_linear_rows(M, N, n, q):
     U.gate(y[None, :], ref.gemm(planes, a16, z16, x), f"from_linear_rows n={n} q={q}")
 
 
+def test_constant_row_and_single_outlier_row():
+    """Degenerate rows: a constant row (Eq. 7's interval is empty: scale 1, integers 0, error 0) and a row
+    that is constant except for one large weight."""
+    M, N, n, q, grid = 6, 128, 3, 2, 4
+    W32, H32 = _layer(M, N, seed=11)
+    W32[2] = np.float32(-0.0421)
+    W32[4] = np.float32(0.01)
+    W32[4, 77] = np.float32(0.9)
+    S_o, b_o, p_o, e_o = quantizer.search(W32, H32, n, q, grid)
+    S_g, b_g, lab_g, e_g = _gpu_search(W32, H32, n, q, grid)
+    parts = fuse.all_partitions(n, q)
+    assert S_g[2] == 1.0 and b_g[2] == W32[2, 0] and e_g[2] == 0.0 and _partition_of(lab_g[2]) == parts[0]
+    assert np.array_equal(b_g, b_o.astype(np.float32))
+    for m in range(M):
+        assert _partition_of(lab_g[m]) == parts[p_o[m]] and S_g[m] == np.float32(S_o[m]), m
+    assert np.allclose(e_g, e_o, rtol=1e-4, atol=0)
+    U32 = quantizer.cholesky_factor(H32).astype(np.float32)
+    w_int = torch.full((M, N), 255, dtype=torch.uint8, device="cuda")
+    ws = torch.empty(bcq.quant_workspace_bytes(M, N), dtype=torch.uint8, device="cuda")
+    bcq.quant_gptq(M, N, n, q, _dev(W32), _dev(U32), _dev(S_g), _dev(b_g), _dev(lab_g), w_int, ws)
+    torch.cuda.synchronize()
+    Wq = w_int.cpu().numpy()
+    assert (Wq[2] == 0).all()
+    choices = [fuse.bcchoice(parts[i], n) for i in p_o]
+    Wq_o = quantizer.gptq(W32, H32, S_g.astype(np.float64), b_g.astype(np.float64), choices, n)
+    assert np.array_equal(Wq[4], Wq_o[4]) and Wq[4, 77] == Wq[4].max() > 0
+
+
 def test_many_column_blocks():
     """A layer wide enough for 16 blocks of the GPTQ pass and 32 column tiles of the quadratic form;
     the oracle runs on sampled rows (rows are independent in both steps)."""

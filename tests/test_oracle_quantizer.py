@@ -134,3 +134,18 @@ def test_search_then_fuse_round_trip():
         signs = np.stack([2.0 * ((planes[i, 0, :, None] >> np.arange(32)) & 1).reshape(-1) - 1 for i in range(q)])
         w_hat = (alpha[0, 0][:, None] * signs).sum(0) + z[0, 0]
         assert np.allclose(w_hat, S[m] * Wq[0] + b[m], rtol=1e-12, atol=1e-15)
+
+
+def test_constant_row_is_reproduced():
+    """Degenerate case: W_max = W_min leaves Eq. 7's interval empty; the row is then reproduced exactly
+    (scale 1, integers 0, qbias = the constant)."""
+    rng = np.random.default_rng(3)
+    W = rng.standard_normal((3, 32)) * 0.02
+    W[1] = 0.0173
+    H = Q.hessian(rng.standard_normal((32, 64)))
+    S, b, p, e = Q.search(W, H, 3, 2, 4)
+    assert S[1] == 1.0 and b[1] == 0.0173 and e[1] == 0.0 and p[1] == 0
+    parts = fuse.all_partitions(3, 2)
+    choices = [fuse.bcchoice(parts[i], 3) for i in p]
+    Wq = Q.gptq(W, H, S, b, choices, 3)
+    assert (Wq[1] == 0).all()
