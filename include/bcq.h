@@ -129,8 +129,11 @@ bcq_status bcq_from_linear(int32_t M, int32_t N, int32_t group, int32_t n_bits, 
 
 /*
  * The quantiser itself, for one layer with row-wise parameters (Sec. II-A Eq. 1-2, Sec. II-B Eq. 5-6,
- * Sec. II-C Eq. 7 and the algorithm closing Sec. II-D).  Offline tooling, three steps:
+ * Sec. II-C Eq. 7 and the algorithm closing Sec. II-D).  Offline tooling, in steps:
  *
+ *   bcq_quant_hessian  H += 2 X^T X for T more calibration inputs X [T][N] (Sec. II-A: H = 2 X X^T with the
+ *                      paper's X = inputs as columns); H DEVICE [N][N] in/out, zero it before the first batch;
+ *                      X and H binary32, 16-byte aligned.  Optional: H may come from anywhere.
  *   bcq_quant_search   per row: qbias = min w; the scale S' on `grid` equidistant points inside
  *                      ((max-min)/(2^(n_bits+1)-1), (max-min)/(2^(n_bits-1)-1)) (Eq. 7) and the tying
  *                      of the n_bits linear planes into q classes (Eq. 10) that minimise the output
@@ -159,6 +162,7 @@ bcq_status bcq_from_linear(int32_t M, int32_t N, int32_t group, int32_t n_bits, 
  * on the matrix cores (v_mfma_f32_32x32x2_f32).
  */
 size_t bcq_quant_workspace_bytes(int32_t M, int32_t N);
+bcq_status bcq_quant_hessian(int32_t N, int32_t T, const float *X, float *H, void *stream);
 bcq_status bcq_quant_search(int32_t M, int32_t N, int32_t n_bits, int32_t q, int32_t grid, const float *W,
                             const float *H, float *S, float *qbias, int8_t *class_of_plane, float *err,
                             void *workspace, void *stream);

@@ -125,6 +125,14 @@ size_t bcq_quant_workspace_bytes(int32_t M, int32_t N)
     return quant_workspace_bytes(M, N);
 }
 
+bcq_status bcq_quant_hessian(int32_t N, int32_t T, const float *X, float *H, void *stream)
+{
+    if (N <= 0 || T <= 0 || N % 4 != 0) return BCQ_ERR_INVALID_ARG;
+    if (N > 32768) return BCQ_ERR_UNSUPPORTED;
+    if (!X || !H || !aligned(X, 16) || !aligned(H, 16)) return BCQ_ERR_INVALID_ARG;
+    return launch_quant_hessian(N, T, X, H, static_cast<hipStream_t>(stream)) == hipSuccess ? BCQ_OK : BCQ_ERR_HIP;
+}
+
 bcq_status bcq_quant_search(int32_t M, int32_t N, int32_t n_bits, int32_t q, int32_t grid, const float *W,
                             const float *H, float *S, float *qbias, int8_t *class_of_plane, float *err,
                             void *workspace, void *stream)

@@ -156,9 +156,10 @@ __global__ void transpose_kernel(int M, int Mp, int N, const float *__restrict__
 // is multiplied.  What happens to the finished tile is the caller's epilogue:
 //   kQuadForm   part[tile row][c] = sum over the tile's rows r of C[r][c] * E[r][c]   (E pitch ldb)
 //   kSubtract   Out[r][c] -= C[r][c]                                                  (Out pitch ldb)
+//   kAddTwice   Out[r][c] += 2 C[r][c]                                                (Out pitch ldb)
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4v __attribute__((ext_vector_type(4)));
-enum { kQuadForm = 0, kSubtract = 1 };
+enum { kQuadForm = 0, kSubtract = 1, kAddTwice = 2 };
 constexpr int kTile = 128, kStep = 16;
 
 __device__ __forceinline__ f32x4v load4_or_zero(const float *base, size_t pitch, int k, int K, int x, int X)
@@ -232,7 +233,7 @@ __global__ __launch_bounds__(256) void mfma_kmajor_kernel(const float *__restric
     }
 
     // element i of a 32 x 32 accumulator: row 8 (i/4) + 4 hi + i%4, column lo
-    if constexpr (MODE == kSubtract) {
+    if constexpr (MODE == kSubtract || MODE == kAddTwice) {
 #pragma unroll
         for (int a = 0; a < 2; ++a)
 #pragma unroll
@@ -241,7 +242,10 @@ __global__ __launch_bounds__(256) void mfma_kmajor_kernel(const float *__restric
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
                     const int r = r0 + wr * 64 + a * 32 + 8 * (i >> 2) + 4 * hi + (i & 3);
-                    if (r < R && c < C) out[(size_t)r * ldb + c] -= acc[a][b][i];
+                    if (r < R && c < C) {
+                        if (MODE == kSubtract) out[(size_t)r * ldb + c] -= acc[a][b][i];
+                        else out[(size_t)r * ldb + c] += 2.0f * acc[a][b][i];
+                    }
                 }
             }
     } else {
@@ -263,6 +267,17 @@ __global__ __launch_bounds__(256) void mfma_kmajor_kernel(const float *__restric
         __syncthreads();
         if (tid < kTile && c0 + tid < C) out[(size_t)blockIdx.y * ldb + c0 + tid] = red[tid] + red[kTile + tid];
     }
+}
+
+// ---------------------------------------------------------------------------------
+// Hessian of the layer-wise objective (Sec. II-A): H += 2 X^T X for T more calibration inputs
+// ---------------------------------------------------------------------------------
+hipError_t launch_quant_hessian(int N, int T, const float *X, float *H, hipStream_t stream)
+{
+    // X is [T][N]: k-major for both operands, C[r][c] = sum_t X[t][r] X[t][c]
+    hipLaunchKernelGGL((mfma_kmajor_kernel<kAddTwice>), dim3((N + kTile - 1) / kTile, (N + kTile - 1) / kTile), dim3(256),
+                       0, stream, X, N, N, X, N, N, T, H, nullptr);
+    return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------------

@@ -77,9 +77,11 @@ def _main():
     W = torch.randn((M, N), device="cuda", generator=g) * 0.02
     X = torch.randn((N, 2 * N), device="cuda", generator=g) + 0.5 * (
         torch.randn((N, 8), device="cuda", generator=g) @ torch.randn((8, 2 * N), device="cuda", generator=g))
-    H = 2 * (X @ X.T)
-    H = (H + H.T) / 2
+    H = torch.zeros((N, N), dtype=torch.float32, device="cuda")
+    Xt = X.T.contiguous()                      # [sample][channel]
     del X
+    B.quant_hessian(N, Xt.shape[0], Xt, H)     # H = 2 X X^T (Sec. II-A)
+    del Xt
     timings = {}
     layer, info = quantize_layer(W, H, a.bits, a.planes, a.grid, timings=timings)
     # output error of the packed layer on the calibration statistics, relative to the layer's output energy

@@ -165,6 +165,11 @@ def test_quantizer_argument_checks():
     assert L.bcq_quant_workspace_bytes(0, 64) == 0
     need = L.bcq_quant_workspace_bytes(70, 160)
     assert need >= 4 * (2 * 160 * 72 + 2 * 72 + 3 * 72 + 128 * 72) and need % 256 == 0   # row pitch 72
+    assert L.bcq_quant_hessian(64, 0, ok, ok, None) == B.BCQ_ERR_INVALID_ARG
+    assert L.bcq_quant_hessian(66, 8, ok, ok, None) == B.BCQ_ERR_INVALID_ARG
+    assert L.bcq_quant_hessian(64, 8, None, ok, None) == B.BCQ_ERR_INVALID_ARG
+    assert L.bcq_quant_hessian(64, 8, ok, ok + 4, None) == B.BCQ_ERR_INVALID_ARG
+    assert L.bcq_quant_hessian(1 << 16, 8, ok, ok, None) == B.BCQ_ERR_UNSUPPORTED
     search = lambda M, N, n, q, grid, *p: L.bcq_quant_search(M, N, n, q, grid, *(p or (ok,) * 7), None)
     assert search(0, 64, 3, 2, 4) == B.BCQ_ERR_INVALID_ARG
     assert search(8, 64, 1, 1, 4) == B.BCQ_ERR_INVALID_ARG              # Eq. 7 needs n >= 2

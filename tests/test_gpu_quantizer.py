@@ -159,6 +159,24 @@ def test_from_linear_rows(M, N, n, q):
     U.gate(y[None, :], ref.gemm(planes, a16, z16, x), f"from_linear_rows n={n} q={q}")
 
 
+@pytest.mark.parametrize("N,T", [(160, 300), (256, 64), (72, 1000)])
+def test_hessian(N, T):
+    """H = 2 X X^T (Sec. II-A) accumulated over two batches of inputs, against the oracle in binary64."""
+    rng = np.random.default_rng(N + T)
+    X = (rng.standard_normal((N, T)) * (1 + 5 * (rng.random((N, 1)) < 0.05))).astype(np.float32)   # [N][T], paper's orientation
+    H_o = quantizer.hessian(X)
+    Xt = _dev(X.T)                                                                                 # [T][N] for the device
+    H = torch.zeros((N, N), dtype=torch.float32, device="cuda")
+    T1 = T // 3
+    bcq.quant_hessian(N, T1, Xt[:T1], H)
+    bcq.quant_hessian(N, T - T1, Xt[T1:], H)
+    torch.cuda.synchronize()
+    H_g = H.cpu().numpy().astype(np.float64)
+    scale = np.sqrt(np.outer(np.diag(H_o), np.diag(H_o)))
+    assert np.abs(H_g - H_o).max() <= 1e-5 * scale.max() and (np.abs(H_g - H_o) / scale).max() <= 1e-5
+    assert np.array_equal(H_g, H_g.T)
+
+
 def test_constant_row_and_single_outlier_row():
     """Degenerate rows: a constant row (Eq. 7's interval is empty: scale 1, integers 0, error 0) and a row
     that is constant except for one large weight."""
