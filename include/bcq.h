@@ -134,6 +134,10 @@ bcq_status bcq_from_linear(int32_t M, int32_t N, int32_t group, int32_t n_bits, 
  *   bcq_quant_hessian  H += 2 X^T X for T more calibration inputs X [T][N] (Sec. II-A: H = 2 X X^T with the
  *                      paper's X = inputs as columns); H DEVICE [N][N] in/out, zero it before the first batch;
  *                      X and H binary32, 16-byte aligned.  Optional: H may come from anywhere.
+ *   bcq_quant_factor   U = the upper triangular factor with (H + damp * mean(diag H) * I)^-1 = U^T U, in binary32
+ *                      (H is not modified; needs H positive definite after dampening, otherwise U holds NaNs);
+ *                      workspace DEVICE, bcq_quant_factor_workspace_bytes(N) bytes, 16-byte aligned, no init.
+ *                      Optional: U may come from any linear-algebra library.
  *   bcq_quant_search   per row: qbias = min w; the scale S' on `grid` equidistant points inside
  *                      ((max-min)/(2^(n_bits+1)-1), (max-min)/(2^(n_bits-1)-1)) (Eq. 7) and the tying
  *                      of the n_bits linear planes into q classes (Eq. 10) that minimise the output
@@ -143,12 +147,13 @@ bcq_status bcq_from_linear(int32_t M, int32_t N, int32_t group, int32_t n_bits, 
  *                      first with the smallest error wins.
  *   bcq_quant_gptq     the column-by-column pass with error compensation (Eq. 1-2) using those
  *                      parameters; U is the upper Cholesky factor of the inverse (dampened) Hessian,
- *                      H^-1 = U^T U, which the caller computes with any linear-algebra library.
+ *                      H^-1 = U^T U (bcq_quant_factor, or any linear-algebra library).
  *   bcq_from_linear_rows   bcq_from_linear with one tying per row and one scaling group per row
  *                      (use group = N and has_offset = 1 for bcq_pack).
  *
  *   W   DEVICE [M][N] binary32 weights (not modified)
- *   H   DEVICE [N][N] binary32, 2 X X^T of the calibration inputs, 16-byte aligned
+ *   H   DEVICE [N][N] binary32, 2 X X^T of the calibration inputs, symmetric (bcq_quant_search reads only its
+ *       upper triangle), 16-byte aligned
  *   U   DEVICE [N][N] binary32, upper triangular, 16-byte aligned
  *   S, qbias DEVICE [M] binary32 (out of search, in of the others)
  *   class_of_plane DEVICE [M][n_bits] int8: class (0..q-1) of bit i of row m (out of search)
@@ -163,6 +168,8 @@ bcq_status bcq_from_linear(int32_t M, int32_t N, int32_t group, int32_t n_bits, 
  */
 size_t bcq_quant_workspace_bytes(int32_t M, int32_t N);
 bcq_status bcq_quant_hessian(int32_t N, int32_t T, const float *X, float *H, void *stream);
+size_t bcq_quant_factor_workspace_bytes(int32_t N);
+bcq_status bcq_quant_factor(int32_t N, float damp, const float *H, float *U, void *workspace, void *stream);
 bcq_status bcq_quant_search(int32_t M, int32_t N, int32_t n_bits, int32_t q, int32_t grid, const float *W,
                             const float *H, float *S, float *qbias, int8_t *class_of_plane, float *err,
                             void *workspace, void *stream);

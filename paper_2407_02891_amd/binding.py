@@ -13,7 +13,7 @@ BCQ_LAYOUT_VERSION = 2
 BCQ_MAX_BATCH = 64
 
 EXPORTS = ["bcq_packed_bytes", "bcq_workspace_bytes", "bcq_workspace_init", "bcq_pack",
-           "bcq_pack_rows", "bcq_from_linear", "bcq_quant_workspace_bytes", "bcq_quant_hessian", "bcq_quant_search",
+           "bcq_pack_rows", "bcq_from_linear", "bcq_quant_workspace_bytes", "bcq_quant_hessian", "bcq_quant_factor_workspace_bytes", "bcq_quant_factor", "bcq_quant_search",
            "bcq_quant_gptq", "bcq_from_linear_rows", "bcq_unpack", "bcq_gemv", "bcq_gemm_skinny", "bcq_read_probe_sink_bytes",
            "bcq_read_probe", "bcq_set_option", "bcq_status_string"]
 
@@ -53,6 +53,9 @@ def lib():
         L.bcq_from_linear.argtypes = [i32, i32, i32, i32, i32, ctypes.POINTER(ctypes.c_int32), vp, vp, vp, vp, vp, vp, vp]
         L.bcq_quant_workspace_bytes.restype, L.bcq_quant_workspace_bytes.argtypes = sz, [i32, i32]
         L.bcq_quant_hessian.restype, L.bcq_quant_hessian.argtypes = i32, [i32, i32, vp, vp, vp]
+        L.bcq_quant_factor_workspace_bytes.restype, L.bcq_quant_factor_workspace_bytes.argtypes = sz, [i32]
+        L.bcq_quant_factor.restype = i32
+        L.bcq_quant_factor.argtypes = [i32, ctypes.c_float, vp, vp, vp, vp]
         L.bcq_quant_search.restype = i32
         L.bcq_quant_search.argtypes = [i32, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]
         L.bcq_quant_gptq.restype = i32
@@ -136,6 +139,15 @@ def quant_workspace_bytes(M, N):
 
 def quant_hessian(N, T, X, H, stream=None):
     _check(lib().bcq_quant_hessian(int(N), int(T), _ptr(X), _ptr(H), _stream(stream)), "bcq_quant_hessian")
+
+
+def quant_factor_workspace_bytes(N):
+    return int(lib().bcq_quant_factor_workspace_bytes(int(N)))
+
+
+def quant_factor(N, damp, H, U, workspace, stream=None):
+    _check(lib().bcq_quant_factor(int(N), float(damp), _ptr(H), _ptr(U), _ptr(workspace), _stream(stream)),
+           "bcq_quant_factor")
 
 
 def quant_search(M, N, n_bits, q, grid, W, H, S, qbias, class_of_plane, err, workspace, stream=None):

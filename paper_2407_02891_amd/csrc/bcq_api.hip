@@ -133,6 +133,22 @@ bcq_status bcq_quant_hessian(int32_t N, int32_t T, const float *X, float *H, voi
     return launch_quant_hessian(N, T, X, H, static_cast<hipStream_t>(stream)) == hipSuccess ? BCQ_OK : BCQ_ERR_HIP;
 }
 
+size_t bcq_quant_factor_workspace_bytes(int32_t N)
+{
+    if (N <= 0 || N % 4 != 0 || N > 32768) return 0;
+    return quant_factor_workspace_bytes(N);
+}
+
+bcq_status bcq_quant_factor(int32_t N, float damp, const float *H, float *U, void *workspace, void *stream)
+{
+    if (N <= 0 || N % 4 != 0 || !(damp >= 0.0f)) return BCQ_ERR_INVALID_ARG;
+    if (N > 32768) return BCQ_ERR_UNSUPPORTED;
+    if (!H || !U || !aligned(H, 16) || !aligned(U, 16)) return BCQ_ERR_INVALID_ARG;
+    if (!workspace || !aligned(workspace, 16)) return BCQ_ERR_WORKSPACE;
+    return launch_quant_factor(N, damp, H, U, workspace, static_cast<hipStream_t>(stream)) == hipSuccess ? BCQ_OK
+                                                                                                       : BCQ_ERR_HIP;
+}
+
 bcq_status bcq_quant_search(int32_t M, int32_t N, int32_t n_bits, int32_t q, int32_t grid, const float *W,
                             const float *H, float *S, float *qbias, int8_t *class_of_plane, float *err,
                             void *workspace, void *stream)

@@ -21,6 +21,8 @@ hipError_t launch_from_linear(int M, int N, int group, int n_bits, int q, const 
                               uint16_t *alpha, uint16_t *offset, hipStream_t stream);
 // The quantiser (row-wise parameters): search over scales and plane tyings, GPTQ pass, fusion.
 size_t quant_workspace_bytes(int M, int N);
+size_t quant_factor_workspace_bytes(int N);
+hipError_t launch_quant_factor(int N, float damp, const float *H, float *U, void *workspace, hipStream_t stream);
 hipError_t launch_quant_hessian(int N, int T, const float *X, float *H, hipStream_t stream);
 hipError_t launch_quant_search(int M, int N, int n_bits, int q, int grid, const float *W, const float *H, float *S,
                                float *qbias, int8_t *labels, float *err_out, void *workspace, hipStream_t stream);

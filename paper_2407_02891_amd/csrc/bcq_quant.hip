@@ -154,12 +154,15 @@ __global__ void transpose_kernel(int M, int Mp, int N, const float *__restrict__
 // quarter as 2 x 2 v_mfma_f32_32x32x2_f32 accumulators; the operand tiles (16 k x 128) go through
 // LDS, double-buffered, the next pair of tiles travelling through registers while the current one
 // is multiplied.  What happens to the finished tile is the caller's epilogue:
-//   kQuadForm   part[tile row][c] = sum over the tile's rows r of C[r][c] * E[r][c]   (E pitch ldb)
-//   kSubtract   Out[r][c] -= C[r][c]                                                  (Out pitch ldb)
-//   kAddTwice   Out[r][c] += 2 C[r][c]                                                (Out pitch ldb)
+//   kQuadForm   part[tile row][c] = sum over the tile's rows r of C[r][c] * E[r][c]; A symmetric, E = B
+//               (the k range stops at the tile's last row, see the loader)
+//   kSubtract   Out[r][c] -= C[r][c]
+//   kAddTwice   Out[r][c] += 2 C[r][c]
+//   kStore      Out[r][c] = C[r][c];   kStoreNegated   Out[r][c] = -C[r][c]
+// (Out and E have pitch ldo; for kQuadForm Out is [tile row][ldo].)
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4v __attribute__((ext_vector_type(4)));
-enum { kQuadForm = 0, kSubtract = 1, kAddTwice = 2 };
+enum { kQuadForm = 0, kSubtract = 1, kAddTwice = 2, kStore = 3, kStoreNegated = 4 };
 constexpr int kTile = 128, kStep = 16;
 
 __device__ __forceinline__ f32x4v load4_or_zero(const float *base, size_t pitch, int k, int K, int x, int X)
@@ -171,14 +174,16 @@ __device__ __forceinline__ f32x4v load4_or_zero(const float *base, size_t pitch,
 template <int MODE>
 __global__ __launch_bounds__(256) void mfma_kmajor_kernel(const float *__restrict__ A, int lda, int R,
                                                           const float *__restrict__ B, int ldb, int C, int K,
-                                                          float *__restrict__ out, const float *__restrict__ E)
+                                                          float *__restrict__ out, int ldo, const float *__restrict__ E)
 {
     __shared__ __attribute__((aligned(16))) float As[2][kStep][kTile];
     __shared__ __attribute__((aligned(16))) float Bs[2][kStep][kTile];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int lo = lane & 31, hi = lane >> 5;
     const int wr = wave >> 1, wc = wave & 1;
-    const int r0 = blockIdx.y * kTile, c0 = blockIdx.x * kTile;
+    // kQuadForm: the tile rows with the longest k range are dispatched first
+    const int tile_row = MODE == kQuadForm ? (int)(gridDim.y - 1 - blockIdx.y) : (int)blockIdx.y;
+    const int r0 = tile_row * kTile, c0 = blockIdx.x * kTile;
     // loader: thread t brings rows t/32 and t/32 + 8 of a 16 x 128 tile, four floats at column 4 (t%32)
     const int lk = tid >> 5, lx = (tid & 31) * 4;
 
@@ -190,11 +195,25 @@ __global__ __launch_bounds__(256) void mfma_kmajor_kernel(const float *__restric
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.0f;
 
+    // kQuadForm: A is symmetric (the Hessian) and the caller wants sum_r E[r][c] C[r][c] with E = B, i.e.
+    // b^T A b: the terms k > r are folded onto k < r (weight 2, diagonal 1), which halves the k range.
+    const int Kend = MODE == kQuadForm ? (K < r0 + kTile ? K : r0 + kTile) : K;
+    auto load_a = [&](int k) {
+        f32x4v v = load4_or_zero(A, lda, k, Kend, r0 + lx, R);
+        if (MODE == kQuadForm) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int r = r0 + lx + e;
+                v[e] *= k < r ? 2.0f : (k == r ? 1.0f : 0.0f);
+            }
+        }
+        return v;
+    };
     f32x4v ra[2], rb[2];
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
-        ra[h] = load4_or_zero(A, lda, lk + 8 * h, K, r0 + lx, R);
-        rb[h] = load4_or_zero(B, ldb, lk + 8 * h, K, c0 + lx, C);
+        ra[h] = load_a(lk + 8 * h);
+        rb[h] = load4_or_zero(B, ldb, lk + 8 * h, Kend, c0 + lx, C);
     }
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
@@ -203,13 +222,13 @@ __global__ __launch_bounds__(256) void mfma_kmajor_kernel(const float *__restric
     }
     __syncthreads();
     int buf = 0;
-    for (int k0 = 0; k0 < K; k0 += kStep) {
-        const bool more = k0 + kStep < K;
+    for (int k0 = 0; k0 < Kend; k0 += kStep) {
+        const bool more = k0 + kStep < Kend;
         if (more) {
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                ra[h] = load4_or_zero(A, lda, k0 + kStep + lk + 8 * h, K, r0 + lx, R);
-                rb[h] = load4_or_zero(B, ldb, k0 + kStep + lk + 8 * h, K, c0 + lx, C);
+                ra[h] = load_a(k0 + kStep + lk + 8 * h);
+                rb[h] = load4_or_zero(B, ldb, k0 + kStep + lk + 8 * h, Kend, c0 + lx, C);
             }
         }
 #pragma unroll
@@ -233,7 +252,7 @@ __global__ __launch_bounds__(256) void mfma_kmajor_kernel(const float *__restric
     }
 
     // element i of a 32 x 32 accumulator: row 8 (i/4) + 4 hi + i%4, column lo
-    if constexpr (MODE == kSubtract || MODE == kAddTwice) {
+    if constexpr (MODE != kQuadForm) {
 #pragma unroll
         for (int a = 0; a < 2; ++a)
 #pragma unroll
@@ -243,8 +262,11 @@ __global__ __launch_bounds__(256) void mfma_kmajor_kernel(const float *__restric
                 for (int i = 0; i < 16; ++i) {
                     const int r = r0 + wr * 64 + a * 32 + 8 * (i >> 2) + 4 * hi + (i & 3);
                     if (r < R && c < C) {
-                        if (MODE == kSubtract) out[(size_t)r * ldb + c] -= acc[a][b][i];
-                        else out[(size_t)r * ldb + c] += 2.0f * acc[a][b][i];
+                        float *o = out + (size_t)r * ldo + c;
+                        if (MODE == kSubtract) *o -= acc[a][b][i];
+                        if (MODE == kAddTwice) *o += 2.0f * acc[a][b][i];
+                        if (MODE == kStore) *o = acc[a][b][i];
+                        if (MODE == kStoreNegated) *o = -acc[a][b][i];
                     }
                 }
             }
@@ -259,13 +281,13 @@ __global__ __launch_bounds__(256) void mfma_kmajor_kernel(const float *__restric
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
                     const int r = r0 + wr * 64 + a * 32 + 8 * (i >> 2) + 4 * hi + (i & 3);
-                    if (r < R && c < C) sum = fmaf(acc[a][b][i], E[(size_t)r * ldb + c], sum);
+                    if (r < R && c < C) sum = fmaf(acc[a][b][i], E[(size_t)r * ldo + c], sum);
                 }
             sum += __shfl_xor(sum, 32);
             if (hi == 0) red[wr * kTile + wc * 64 + b * 32 + lo] = sum;
         }
         __syncthreads();
-        if (tid < kTile && c0 + tid < C) out[(size_t)blockIdx.y * ldb + c0 + tid] = red[tid] + red[kTile + tid];
+        if (tid < kTile && c0 + tid < C) out[(size_t)tile_row * ldo + c0 + tid] = red[tid] + red[kTile + tid];
     }
 }
 
@@ -276,7 +298,181 @@ hipError_t launch_quant_hessian(int N, int T, const float *X, float *H, hipStrea
 {
     // X is [T][N]: k-major for both operands, C[r][c] = sum_t X[t][r] X[t][c]
     hipLaunchKernelGGL((mfma_kmajor_kernel<kAddTwice>), dim3((N + kTile - 1) / kTile, (N + kTile - 1) / kTile), dim3(256),
-                       0, stream, X, N, N, X, N, N, T, H, nullptr);
+                       0, stream, X, N, N, X, N, N, T, H, N, nullptr);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------
+// U with (H + lambda I)^-1 = U^T U, U upper triangular: what the GPTQ pass reads (Eq. 2)
+// ---------------------------------------------------------------------------------
+// With H_d = H + lambda I = R R^T, R UPPER triangular (a Cholesky factorisation taken from the last
+// row upwards), H_d^-1 = R^-T R^-1, so U = R^-1.  Both steps are blocked by 128 columns; the diagonal
+// blocks are factored and inverted by one workgroup in LDS, everything else is the k-major product
+// above (K = 128 panels and trailing updates for R; growing K for the off-diagonal blocks of U).
+// Working matrices (binary32, pitch N): Hw = H_d (consumed), Rt = R^T, Ut = U^T, T = one panel.
+constexpr int kFactorBlock = 128;
+
+__global__ void diag_mean_kernel(int N, const float *__restrict__ H, float damp, float *__restrict__ lambda)
+{
+    __shared__ float part[256];
+    float s = 0.0f;
+    for (int i = threadIdx.x; i < N; i += 256) s += H[(size_t)i * N + i];
+    part[threadIdx.x] = s;
+    __syncthreads();
+    for (int k = 128; k > 0; k >>= 1) {
+        if ((int)threadIdx.x < k) part[threadIdx.x] += part[threadIdx.x + k];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *lambda = damp * part[0] / (float)N;
+}
+
+__global__ void damped_copy_kernel(int N, const float *__restrict__ H, const float *__restrict__ lambda,
+                                   float *__restrict__ Hw)
+{
+    const size_t gid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (gid >= (size_t)N * N) return;
+    const int i = (int)(gid / N), j = (int)(gid - (size_t)i * N);
+    Hw[gid] = H[gid] + (i == j ? *lambda : 0.0f);
+}
+
+// Diagonal block [r0, r0 + b): D = R R^T in place (R upper, from the last column to the first), then
+// R^-1 in place (column by column); writes the block of U and of U^T.  One workgroup; the block sits
+// in LDS with an odd pitch so that rows and columns are both conflict-free.
+constexpr int kDiagPitch = kFactorBlock + 1;
+constexpr int kDiagLdsBytes = kFactorBlock * kDiagPitch * 4;  // 66048: dynamic, above the static limit
+
+__global__ __launch_bounds__(256) void factor_diag_kernel(int N, int r0, int b, const float *__restrict__ Hw,
+                                                          float *__restrict__ U, float *__restrict__ Ut)
+{
+    extern __shared__ float D[];
+    const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+    for (int e = tid; e < b * b; e += 256) {
+        const int i = e / b, l = e - i * b;
+        D[i * kDiagPitch + l] = Hw[(size_t)(r0 + i) * N + r0 + l];
+    }
+    __syncthreads();
+    // column j of R = column j of the remaining block / sqrt(its corner); then the corner's rank-1 update.
+    // D[j][j] keeps the un-rooted corner until the end (nobody reads it after step j).
+    for (int j = b - 1; j >= 0; --j) {
+        const float d = sqrtf(D[j * kDiagPitch + j]);
+        if (tid < j) D[tid * kDiagPitch + j] /= d;  // own element: read and written by this thread only
+        __syncthreads();
+        for (int i = ty; i < j; i += 16) {  // D[i][l] -= R[i][j] R[l][j] for i <= l < j
+            const float ri = D[i * kDiagPitch + j];
+            for (int l = tx; l < j; l += 16)
+                if (i <= l) D[i * kDiagPitch + l] -= ri * D[l * kDiagPitch + j];
+        }
+        __syncthreads();
+    }
+    if (tid < b) D[tid * kDiagPitch + tid] = sqrtf(D[tid * kDiagPitch + tid]);
+    __syncthreads();
+    // V = R^-1 in place: V[0:j][j] = -V[0:j][0:j] R[0:j][j] / R[j][j]; two threads share a row's dot product
+    const int row = tid >> 1, half = tid & 1;
+    for (int j = 0; j < b; ++j) {
+        const float vjj = 1.0f / D[j * kDiagPitch + j];
+        float s = 0.0f;
+        if (row < j) {
+            const int len = j - row, cut = row + (len + 1) / 2;
+            const int m0 = half ? cut : row, m1 = half ? j : cut;
+            for (int m = m0; m < m1; ++m) s = fmaf(D[row * kDiagPitch + m], D[m * kDiagPitch + j], s);
+        }
+        s += __shfl_xor(s, 1);
+        __syncthreads();
+        if (half == 0) {
+            if (row < j) D[row * kDiagPitch + j] = -s * vjj;
+            else if (row == j) D[j * kDiagPitch + j] = vjj;
+        }
+        __syncthreads();
+    }
+    for (int e = tid; e < b * b; e += 256) {
+        const int i = e / b, l = e - i * b;
+        const float v = i <= l ? D[i * kDiagPitch + l] : 0.0f;
+        U[(size_t)(r0 + i) * N + r0 + l] = v;
+        Ut[(size_t)(r0 + l) * N + r0 + i] = v;
+    }
+}
+
+// dst[c][r] = src[r][c] for a rows x cols block.
+__global__ void transpose_block_kernel(int rows, int cols, const float *__restrict__ src, int lds, float *__restrict__ dst,
+                                       int ldd)
+{
+    __shared__ float tile[32][33];
+    const int r0 = blockIdx.y * 32, c0 = blockIdx.x * 32;
+    for (int i = threadIdx.y; i < 32; i += blockDim.y) {
+        const int r = r0 + i, c = c0 + threadIdx.x;
+        tile[i][threadIdx.x] = (r < rows && c < cols) ? src[(size_t)r * lds + c] : 0.0f;
+    }
+    __syncthreads();
+    for (int i = threadIdx.y; i < 32; i += blockDim.y) {
+        const int c = c0 + i, r = r0 + threadIdx.x;
+        if (r < rows && c < cols) dst[(size_t)c * ldd + r] = tile[threadIdx.x][i];
+    }
+}
+
+size_t quant_factor_workspace_bytes(int N)
+{
+    const size_t floats = 3 * (size_t)N * N + 64;
+    return (floats * 4 + 255) / 256 * 256;
+}
+
+template <int MODE>
+static void product(hipStream_t stream, const float *A, int lda, int R, const float *B, int ldb, int C, int K, float *out,
+                    int ldo)
+{
+    hipLaunchKernelGGL((mfma_kmajor_kernel<MODE>), dim3((C + kTile - 1) / kTile, (R + kTile - 1) / kTile), dim3(256), 0,
+                       stream, A, lda, R, B, ldb, C, K, out, ldo, nullptr);
+}
+
+// Off-diagonal blocks of U = R^-1 for the rows / columns [lo, hi) (the diagonal blocks are in place):
+// with the range cut at a block boundary, U12 = -U11 (R12 U22), both factors from the two halves.
+static void invert_range(hipStream_t stream, int N, int lo, int hi, const float *Rt, float *U, float *Ut, float *T)
+{
+    const int nblk = (hi - lo + kFactorBlock - 1) / kFactorBlock;
+    if (nblk <= 1) return;
+    const int mid = lo + (nblk / 2) * kFactorBlock;
+    invert_range(stream, N, lo, mid, Rt, U, Ut, T);
+    invert_range(stream, N, mid, hi, Rt, U, Ut, T);
+    const int rows = mid - lo, cols = hi - mid;
+    // T[i][c] = sum_m R[lo + i][mid + m] U[mid + m][mid + c]
+    product<kStore>(stream, Rt + (size_t)mid * N + lo, N, rows, U + (size_t)mid * N + mid, N, cols, cols, T, cols);
+    // U[lo + r][mid + c] = -sum_j U[lo + r][lo + j] T[j][c]
+    product<kStoreNegated>(stream, Ut + (size_t)lo * N + lo, N, rows, T, cols, cols, rows, U + (size_t)lo * N + mid, N);
+    hipLaunchKernelGGL(transpose_block_kernel, dim3((cols + 31) / 32, (rows + 31) / 32), dim3(32, 8), 0, stream, rows, cols,
+                       U + (size_t)lo * N + mid, N, Ut + (size_t)mid * N + lo, N);
+}
+
+hipError_t launch_quant_factor(int N, float damp, const float *H, float *U, void *workspace, hipStream_t stream)
+{
+    float *Hw = static_cast<float *>(workspace);
+    float *Rt = Hw + (size_t)N * N, *Ut = Rt + (size_t)N * N;
+    float *lambda = Ut + (size_t)N * N;
+    static bool lds_set = false;  // per process; the attribute belongs to the function, not to a device
+    if (!lds_set) {
+        hipError_t a = hipFuncSetAttribute(reinterpret_cast<const void *>(factor_diag_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kDiagLdsBytes);
+        if (a != hipSuccess) return a;
+        lds_set = true;
+    }
+    hipLaunchKernelGGL(diag_mean_kernel, dim3(1), dim3(256), 0, stream, N, H, damp, lambda);
+    hipLaunchKernelGGL(damped_copy_kernel, dim3((unsigned)(((size_t)N * N + 255) / 256)), dim3(256), 0, stream, N, H,
+                       lambda, Hw);
+    hipError_t e = launch_fill_zero(U, (size_t)N * N * 4, stream);
+    if (e != hipSuccess) return e;
+    e = launch_fill_zero(Ut, (size_t)N * N * 4, stream);
+    if (e != hipSuccess) return e;
+    const int nblk = (N + kFactorBlock - 1) / kFactorBlock;
+    // R, from the last block column to the first
+    for (int k = nblk - 1; k >= 0; --k) {
+        const int r0 = k * kFactorBlock, b = N - r0 < kFactorBlock ? N - r0 : kFactorBlock;
+        hipLaunchKernelGGL(factor_diag_kernel, dim3(1), dim3(256), kDiagLdsBytes, stream, N, r0, b, Hw, U, Ut);
+        if (r0 == 0) break;
+        // panel, transposed: Rt[r0 + c][i] = R[i][r0 + c] = sum_m V[c][m] Hw[r0 + m][i]   (Hw symmetric, V = R_kk^-1)
+        product<kStore>(stream, Ut + (size_t)r0 * N + r0, N, b, Hw + (size_t)r0 * N, N, r0, b, Rt + (size_t)r0 * N, N);
+        // Hw[i][j] -= sum_c R[i][r0 + c] R[j][r0 + c] for i, j < r0
+        product<kSubtract>(stream, Rt + (size_t)r0 * N, N, r0, Rt + (size_t)r0 * N, N, r0, b, Hw, N);
+    }
+    // U = R^-1: Hw is free now and holds the intermediate products
+    invert_range(stream, N, 0, N, Rt, U, Ut, Hw);
     return hipGetLastError();
 }
 
@@ -380,10 +576,10 @@ hipError_t launch_quant_search(int M, int N, int n_bits, int q, int grid, const 
         for (const Tying &t : tyings) {
             hipLaunchKernelGGL(delta_kernel, dim3((w.Mp + 255) / 256, N), dim3(256), 0, stream, M, w.Mp, N, n_bits, g,
                                grid, t, w.Wt, w.wmin, w.wmax, w.Dt);
-            // C[l][m] = sum_k H[k][l] Dt[k][m]  (= (d H)[m][l] whether or not H is exactly symmetric:
-            // d H d^T = d H^T d^T), then the dot with Dt[l][m] over each tile's 128 values of l
+            // d H d^T row by row: sum_l Dt[l][m] sum_{k <= l} w_kl H[k][l] Dt[k][m], w = 2 off the diagonal
+            // (only the upper triangle of H is read), one partial per tile of 128 values of l
             hipLaunchKernelGGL((mfma_kmajor_kernel<kQuadForm>), dim3((w.Mp + kTile - 1) / kTile, w.ntile), dim3(256), 0,
-                               stream, H, N, N, w.Dt, w.Mp, w.Mp, N, w.part, w.Dt);
+                               stream, H, N, N, w.Dt, w.Mp, w.Mp, N, w.part, w.Mp, w.Dt);
             hipLaunchKernelGGL(keep_best_kernel, dim3((M + 255) / 256), dim3(256), 0, stream, M, w.Mp, n_bits, w.ntile, g,
                                grid, first ? 1 : 0, t, w.part, w.wmin, w.wmax, w.best, S, qbias, labels);
             first = false;
@@ -471,7 +667,7 @@ hipError_t launch_quant_gptq(int M, int N, int n_bits, int q, const float *W, co
         if (c1 < N)  // Wt[k][m] -= sum_j U[c0 + j][k] Err[j][m] for the columns k >= c1
             hipLaunchKernelGGL((mfma_kmajor_kernel<kSubtract>), dim3((w.Mp + kTile - 1) / kTile, (N - c1 + kTile - 1) / kTile),
                                dim3(256), 0, stream, U + (size_t)c0 * N + c1, N, N - c1, w.Err, w.Mp, w.Mp, c1 - c0,
-                               w.Wt + (size_t)c1 * w.Mp, nullptr);
+                               w.Wt + (size_t)c1 * w.Mp, w.Mp, nullptr);
     }
     return hipGetLastError();
 }

@@ -1,10 +1,9 @@
 """Quantise one linear layer to the packed binary coding with the device quantiser
 (paper Sec. II-A Eq. 1-2, Sec. II-B Eq. 5-6, Sec. II-C Eq. 7, Sec. II-D Eq. 11).
 
-`quantize_layer` chains the C-ABI calls: search (scale grid x plane tyings, per row), GPTQ pass,
-fusion into q sign planes with per-row scales and offset, packing.  The only step done outside the
-library is the factorisation of the inverse Hessian (torch.linalg, binary64): the library takes the
-upper factor U with H^-1 = U^T U as an input.
+`quantize_layer` chains the C-ABI calls: search (scale grid x plane tyings, per row), factorisation
+of the inverse dampened Hessian, GPTQ pass, fusion into q sign planes with per-row scales and offset,
+packing.  Every step runs in the library's kernels; torch only holds the buffers.
 
 Run as a module for a timed demonstration on a synthetic layer:
     python -m paper_2407_02891_amd.quantize --rows 7168 --cols 7168 --bits 3 --planes 2 --grid 8
@@ -19,10 +18,12 @@ from . import binding as B
 
 
 def inverse_hessian_factor(H, damp=0.01):
-    """Upper Cholesky factor of (H + damp * mean(diag H) I)^-1, binary32 on H's device."""
-    Hd = H.double()
-    Hd = Hd + damp * Hd.diagonal().mean() * torch.eye(H.shape[0], device=H.device, dtype=torch.float64)
-    return torch.linalg.cholesky(torch.linalg.inv(Hd)).T.contiguous().float()
+    """Upper triangular U with (H + damp * mean(diag H) I)^-1 = U^T U, binary32 on H's device."""
+    N = H.shape[0]
+    U = torch.empty((N, N), dtype=torch.float32, device=H.device)
+    ws = torch.empty(B.quant_factor_workspace_bytes(N), dtype=torch.uint8, device=H.device)
+    B.quant_factor(N, damp, H, U, ws)
+    return U
 
 
 def quantize_layer(W, H, n_bits, q, grid=8, damp=0.01, timings=None):

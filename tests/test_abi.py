@@ -170,6 +170,14 @@ def test_quantizer_argument_checks():
     assert L.bcq_quant_hessian(64, 8, None, ok, None) == B.BCQ_ERR_INVALID_ARG
     assert L.bcq_quant_hessian(64, 8, ok, ok + 4, None) == B.BCQ_ERR_INVALID_ARG
     assert L.bcq_quant_hessian(1 << 16, 8, ok, ok, None) == B.BCQ_ERR_UNSUPPORTED
+    assert L.bcq_quant_factor_workspace_bytes(66) == 0
+    assert L.bcq_quant_factor_workspace_bytes(64) >= 4 * 3 * 64 * 64
+    assert L.bcq_quant_factor(0, 0.01, ok, ok, ok, None) == B.BCQ_ERR_INVALID_ARG
+    assert L.bcq_quant_factor(64, -1.0, ok, ok, ok, None) == B.BCQ_ERR_INVALID_ARG
+    assert L.bcq_quant_factor(64, 0.01, None, ok, ok, None) == B.BCQ_ERR_INVALID_ARG
+    assert L.bcq_quant_factor(64, 0.01, ok, ok + 4, ok, None) == B.BCQ_ERR_INVALID_ARG
+    assert L.bcq_quant_factor(64, 0.01, ok, ok, None, None) == B.BCQ_ERR_WORKSPACE
+    assert L.bcq_quant_factor(1 << 16, 0.01, ok, ok, ok, None) == B.BCQ_ERR_UNSUPPORTED
     search = lambda M, N, n, q, grid, *p: L.bcq_quant_search(M, N, n, q, grid, *(p or (ok,) * 7), None)
     assert search(0, 64, 3, 2, 4) == B.BCQ_ERR_INVALID_ARG
     assert search(8, 64, 1, 1, 4) == B.BCQ_ERR_INVALID_ARG              # Eq. 7 needs n >= 2

@@ -177,6 +177,41 @@ def test_hessian(N, T):
     assert np.array_equal(H_g, H_g.T)
 
 
+@pytest.mark.parametrize("N", [64, 160, 384, 1000])
+def test_inverse_hessian_factor(N):
+    """U with (H + 0.01 mean(diag H) I)^-1 = U^T U, U upper triangular, against the oracle's binary64 factor;
+    the device works in binary32, so the comparison is relative to the size of the entries of U and the
+    defining identity is checked in binary64 from the device's U."""
+    rng = np.random.default_rng(N)
+    _, H32 = _layer(8, N, seed=N)
+    U_o = quantizer.cholesky_factor(H32)
+    U = torch.full((N, N), float("nan"), dtype=torch.float32, device="cuda")
+    ws = torch.empty(bcq.quant_factor_workspace_bytes(N), dtype=torch.uint8, device="cuda")
+    H_dev = _dev(H32)
+    bcq.quant_factor(N, 0.01, H_dev, U, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(H_dev.cpu().numpy(), H32)
+    U_g = U.cpu().numpy().astype(np.float64)
+    assert np.isfinite(U_g).all() and (np.tril(U_g, -1) == 0).all() and (np.diag(U_g) > 0).all()
+    assert np.abs(U_g - U_o).max() <= 2e-4 * np.abs(U_o).max(), np.abs(U_g - U_o).max() / np.abs(U_o).max()
+    Hd = H32.astype(np.float64) + 0.01 * np.mean(np.diag(H32.astype(np.float64))) * np.eye(N)
+    assert np.abs(U_g.T @ U_g @ Hd - np.eye(N)).max() <= 2e-3
+    # and it drives the GPTQ pass to the oracle's integers
+    M, n, q = 24, 3, 2
+    W32 = (rng.standard_normal((M, N)) * 0.02).astype(np.float32)
+    S, b, p, _ = quantizer.search(W32, H32, n, q, grid=3)
+    S32, b32 = S.astype(np.float32), b.astype(np.float32)
+    parts = fuse.all_partitions(n, q)
+    choices = [fuse.bcchoice(parts[i], n) for i in p]
+    labels = np.stack([_labels_of(parts[i], n) for i in p])
+    w_int = torch.empty((M, N), dtype=torch.uint8, device="cuda")
+    ws2 = torch.empty(bcq.quant_workspace_bytes(M, N), dtype=torch.uint8, device="cuda")
+    bcq.quant_gptq(M, N, n, q, _dev(W32), U, _dev(S32), _dev(b32), _dev(labels), w_int, ws2)
+    torch.cuda.synchronize()
+    Wq_o = quantizer.gptq(W32, H32, S32.astype(np.float64), b32.astype(np.float64), choices, n)
+    assert float(np.mean(w_int.cpu().numpy() != Wq_o)) <= 5e-3
+
+
 def test_constant_row_and_single_outlier_row():
     """Degenerate rows: a constant row (Eq. 7's interval is empty: scale 1, integers 0, error 0) and a row
     that is constant except for one large weight."""
