@@ -336,10 +336,38 @@ __global__ void damped_copy_kernel(int N, const float *__restrict__ H, const flo
 }
 
 // Diagonal block [r0, r0 + b): D = R R^T in place (R upper, from the last column to the first), then
-// R^-1 in place (column by column); writes the block of U and of U^T.  One workgroup; the block sits
-// in LDS with an odd pitch so that rows and columns are both conflict-free.
+// R^-1 beside it; writes the block of U and of U^T.  One workgroup; both blocks sit in LDS with an
+// odd pitch so that rows and columns are both conflict-free.
 constexpr int kDiagPitch = kFactorBlock + 1;
-constexpr int kDiagLdsBytes = kFactorBlock * kDiagPitch * 4;  // 66048: dynamic, above the static limit
+constexpr int kDiagLdsBytes = 2 * kFactorBlock * kDiagPitch * 4;  // the block and its inverse, 132096 B: dynamic
+
+// Straight-line (no branch per element, so the LDS reads are issued together): every owned element of
+// the first NM x NM groups is read, changed only where i <= l < j, and written back by its one owner.
+template <int NM>
+__device__ __forceinline__ void corner_update(float *D, int j, int ty, int tx)
+{
+    float ri[NM], rl[NM], v[NM][NM];
+#pragma unroll
+    for (int a = 0; a < NM; ++a) {
+        ri[a] = D[(ty + 16 * a) * kDiagPitch + j];
+        rl[a] = D[(tx + 16 * a) * kDiagPitch + j];
+    }
+#pragma unroll
+    for (int a = 0; a < NM; ++a)
+#pragma unroll
+        for (int c = 0; c < NM; ++c) v[a][c] = D[(ty + 16 * a) * kDiagPitch + tx + 16 * c];
+#pragma unroll
+    for (int a = 0; a < NM; ++a)
+#pragma unroll
+        for (int c = 0; c < NM; ++c) {
+            const int i = ty + 16 * a, l = tx + 16 * c;
+            v[a][c] -= (i <= l && l < j) ? ri[a] * rl[c] : 0.0f;
+        }
+#pragma unroll
+    for (int a = 0; a < NM; ++a)
+#pragma unroll
+        for (int c = 0; c < NM; ++c) D[(ty + 16 * a) * kDiagPitch + tx + 16 * c] = v[a][c];
+}
 
 __global__ __launch_bounds__(256) void factor_diag_kernel(int N, int r0, int b, const float *__restrict__ Hw,
                                                           float *__restrict__ U, float *__restrict__ Ut)
@@ -357,36 +385,39 @@ __global__ __launch_bounds__(256) void factor_diag_kernel(int N, int r0, int b, 
         const float d = sqrtf(D[j * kDiagPitch + j]);
         if (tid < j) D[tid * kDiagPitch + j] /= d;  // own element: read and written by this thread only
         __syncthreads();
-        for (int i = ty; i < j; i += 16) {  // D[i][l] -= R[i][j] R[l][j] for i <= l < j
-            const float ri = D[i * kDiagPitch + j];
-            for (int l = tx; l < j; l += 16)
-                if (i <= l) D[i * kDiagPitch + l] -= ri * D[l * kDiagPitch + j];
+        // D[i][l] -= R[i][j] R[l][j] for i <= l < j; thread (ty, tx) owns i = ty + 16 a, l = tx + 16 c
+        switch ((j + 15) >> 4) {  // uniform: how many 16 x 16 groups reach below j
+            case 1: corner_update<1>(D, j, ty, tx); break;
+            case 2: corner_update<2>(D, j, ty, tx); break;
+            case 3: corner_update<3>(D, j, ty, tx); break;
+            case 4: corner_update<4>(D, j, ty, tx); break;
+            case 5: corner_update<5>(D, j, ty, tx); break;
+            case 6: corner_update<6>(D, j, ty, tx); break;
+            case 7: corner_update<7>(D, j, ty, tx); break;
+            case 8: corner_update<8>(D, j, ty, tx); break;
+            default: break;
         }
         __syncthreads();
     }
     if (tid < b) D[tid * kDiagPitch + tid] = sqrtf(D[tid * kDiagPitch + tid]);
     __syncthreads();
-    // V = R^-1 in place: V[0:j][j] = -V[0:j][0:j] R[0:j][j] / R[j][j]; two threads share a row's dot product
-    const int row = tid >> 1, half = tid & 1;
-    for (int j = 0; j < b; ++j) {
-        const float vjj = 1.0f / D[j * kDiagPitch + j];
-        float s = 0.0f;
-        if (row < j) {
-            const int len = j - row, cut = row + (len + 1) / 2;
-            const int m0 = half ? cut : row, m1 = half ? j : cut;
-            for (int m = m0; m < m1; ++m) s = fmaf(D[row * kDiagPitch + m], D[m * kDiagPitch + j], s);
+    // V = R^-1 into the second half of the LDS block, one thread per column and no barrier: column j of
+    // R V = I from its diagonal upwards, v[i][j] = -(sum_{i < m <= j} r[i][m] v[m][j]) / r[i][i].  In step i
+    // the threads read the same r[i][m] (broadcast) and their own column of V.
+    float *V = D + kFactorBlock * kDiagPitch;
+    if (tid < b) {
+        const int j = tid;
+        V[j * kDiagPitch + j] = 1.0f / D[j * kDiagPitch + j];
+        for (int i = j - 1; i >= 0; --i) {
+            float acc = 0.0f;
+            for (int m = i + 1; m <= j; ++m) acc = fmaf(D[i * kDiagPitch + m], V[m * kDiagPitch + j], acc);
+            V[i * kDiagPitch + j] = -acc / D[i * kDiagPitch + i];
         }
-        s += __shfl_xor(s, 1);
-        __syncthreads();
-        if (half == 0) {
-            if (row < j) D[row * kDiagPitch + j] = -s * vjj;
-            else if (row == j) D[j * kDiagPitch + j] = vjj;
-        }
-        __syncthreads();
     }
+    __syncthreads();
     for (int e = tid; e < b * b; e += 256) {
         const int i = e / b, l = e - i * b;
-        const float v = i <= l ? D[i * kDiagPitch + l] : 0.0f;
+        const float v = i <= l ? V[i * kDiagPitch + l] : 0.0f;
         U[(size_t)(r0 + i) * N + r0 + l] = v;
         Ut[(size_t)(r0 + l) * N + r0 + i] = v;
     }
@@ -619,8 +650,13 @@ __device__ __forceinline__ void row_choice(const int8_t *label, int n_bits, int 
     }
 }
 
-// One block of up to 128 columns [c0, c1): one thread per row, the block's columns of the row in LDS.
-constexpr int kGptqBlock = 128, kGptqRows = 64;
+// One block of up to 128 columns [c0, c1): one thread per row.  The block's columns of the row sit in
+// LDS; the 32 columns being decided are held in registers, where each decision's compensation reaches
+// the later ones of the 32 at once, and reach the block's remaining columns when the 32 are done
+// (the same order of operations per weight as column by column).  The rows of U that the 32 columns
+// need are staged in LDS: the 32 x 32 corner as it is, the part to its right transposed so that one
+// column's 32 factors are contiguous.
+constexpr int kGptqBlock = 128, kGptqRows = 64, kGptqSub = 32;
 __global__ __launch_bounds__(kGptqRows) void gptq_block_kernel(int M, int Mp, int N, int n_bits, int q, int c0, int c1,
                                                                float *__restrict__ Wt, const float *__restrict__ U,
                                                                const float *__restrict__ S, const float *__restrict__ qbias,
@@ -628,6 +664,8 @@ __global__ __launch_bounds__(kGptqRows) void gptq_block_kernel(int M, int Mp, in
                                                                uint8_t *__restrict__ w_int, float *__restrict__ Err)
 {
     __shared__ float wl[kGptqBlock][kGptqRows + 1];
+    __shared__ __attribute__((aligned(16))) float Ud[kGptqSub][kGptqSub];
+    __shared__ __attribute__((aligned(16))) float Uo[kGptqBlock - kGptqSub][kGptqSub];
     const int tm = threadIdx.x, m = blockIdx.x * kGptqRows + tm;
     const bool live = m < M;
     const int cols = c1 - c0;
@@ -638,18 +676,43 @@ __global__ __launch_bounds__(kGptqRows) void gptq_block_kernel(int M, int Mp, in
         s = S[m]; b = qbias[m];
     }
     for (int j = 0; j < cols; ++j) wl[j][tm] = live ? Wt[(size_t)(c0 + j) * Mp + m] : 0.0f;
-    for (int j = 0; j < cols; ++j) {
-        const int c = c0 + j;
-        const float w = wl[j][tm];
-        float e = 0.0f;
-        if (live) {
-            const int wq = quant_int((double)w, s, b, n_bits, choice, 1 << q);
-            w_int[(size_t)m * N + c] = (uint8_t)wq;
-            const float qv = (float)(s * wq + b);
-            e = (w - qv) / U[(size_t)c * N + c];
+    for (int sb = 0; sb < cols; sb += kGptqSub) {
+        const int sw = cols - sb < kGptqSub ? cols - sb : kGptqSub;
+        const int rest = cols - sb - sw;
+        __syncthreads();  // the previous round's readers of Ud / Uo are done
+        for (int e = tm; e < kGptqSub * kGptqSub; e += kGptqRows) {
+            const int i = e >> 5, k = e & 31;
+            Ud[i][k] = (i < sw && k < sw) ? U[(size_t)(c0 + sb + i) * N + c0 + sb + k] : (i == k ? 1.0f : 0.0f);
         }
-        if (m < Mp) Err[(size_t)j * Mp + m] = e;  // zeros in the pad rows
-        for (int k = j + 1; k < cols; ++k) wl[k][tm] = fmaf(-e, U[(size_t)c * N + c0 + k], wl[k][tm]);
+        for (int e = tm; e < rest * kGptqSub; e += kGptqRows) {
+            const int i = e / rest, k = e - i * rest;
+            Uo[k][i] = U[(size_t)(c0 + sb + i) * N + c0 + sb + sw + k];  // rest > 0 only with sw = 32
+        }
+        __syncthreads();
+        float w[kGptqSub], err[kGptqSub];
+#pragma unroll
+        for (int i = 0; i < kGptqSub; ++i) w[i] = i < sw ? wl[sb + i][tm] : 0.0f;
+#pragma unroll
+        for (int i = 0; i < kGptqSub; ++i) {
+            err[i] = 0.0f;
+            if (i < sw) {  // uniform
+                if (live) {
+                    const int wq = quant_int((double)w[i], s, b, n_bits, choice, 1 << q);
+                    w_int[(size_t)m * N + c0 + sb + i] = (uint8_t)wq;
+                    const float qv = (float)(s * wq + b);
+                    err[i] = (w[i] - qv) / Ud[i][i];
+                }
+                if (m < Mp) Err[(size_t)(sb + i) * Mp + m] = err[i];  // zeros in the pad rows
+#pragma unroll
+                for (int k = i + 1; k < kGptqSub; ++k) w[k] = fmaf(-err[i], Ud[i][k], w[k]);
+            }
+        }
+        for (int k = 0; k < rest; ++k) {
+            float a = wl[sb + sw + k][tm];
+#pragma unroll
+            for (int i = 0; i < kGptqSub; ++i) a = fmaf(-err[i], Uo[k][i], a);
+            wl[sb + sw + k][tm] = a;
+        }
     }
 }
 
