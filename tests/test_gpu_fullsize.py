@@ -51,10 +51,12 @@ def test_llama70b_shapes(M, N, q):
 
 
 @pytest.mark.parametrize("M,N,q,offset,batch", [(7168, 7168, 2, True, 8), (9216, 9216, 3, False, 4),
-                                                  (9216, 9216, 3, False, 16), (28672, 7168, 2, True, 8)])
+                                                  (9216, 9216, 3, False, 16), (28672, 7168, 2, True, 8),
+                                                  (36864, 9216, 3, False, 16), (7168, 28672, 3, False, 64)])
 def test_skinny_fullsize(M, N, q, offset, batch):
-    """configs[2] (q=2 with offset, batch 8) and configs[3] (batch 4 and 16, outlier channels)"""
-    _check(M, N, q, offset, batch=batch, outlier_frac=0.01 if M == 9216 else 0.0)
+    """configs[2] (q=2 with offset, batch 8), configs[3] (batch 4 and 16, outlier channels, incl. the tallest
+    layer) and the dominant layer of configs[1] at the widest batch of one pass (64)"""
+    _check(M, N, q, offset, batch=batch, outlier_frac=0.01 if N == 9216 else 0.0)
 
 
 def test_llama70b_fused_qkv_equals_three_gemvs():
