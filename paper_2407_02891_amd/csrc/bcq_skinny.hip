@@ -5,10 +5,10 @@
 // bytes do not, so the path stops being HBM-bound and the sign-sum tables of the batch-1
 // kernel (one table set per activation vector) no longer fit in LDS.  Here every sign becomes
 // a binary16 operand of the matrix cores (v_mfma_f32_16x16x32_f16, fp32 accumulate); the cost
-// is the same for every batch up to 16; wider batches (up to 64, table kernel) reuse the expanded
-// operands for every group of 16 columns.
+// is the same for every batch up to 16; wider batches (up to 64) reuse the expanded operands for
+// every group of 16 columns.
 //
-// Common skeleton (bcq_skinny_kernel<Q, Z, SUB, VER, LDS_STEPS>):
+// Common skeleton (bcq_skinny_kernel<Q, Z, SUB, VER, LDS_STEPS, NB>):
 //  * Same packed blob as the GEMV (bcq_layout.h).  A work unit is (tile group, column slice): the
 //    four waves of a workgroup take the four row tiles of the group and share an LDS copy of the
 //    slice of X (pitch 1040 B: conflict-free ds_read_b128; double-buffered, one barrier per unit).
@@ -251,9 +251,9 @@ __device__ __forceinline__ int owner_of_unit(int u, int units, int groups)
 // ---------------------------------------------------------------------------------
 // VER 1: one tile and slice, alpha folded into A
 // ---------------------------------------------------------------------------------
-template <int Q, int Z, int SUB>
+template <int Q, int Z, int SUB, int NB>
 __device__ __forceinline__ void compute_folded(TileRegs<Q, Z, SUB> &cur, const uint8_t *xs_buf, int r, int h,
-                                               f32x4 (&acc)[2])
+                                               f32x4 (&acc)[NB][2])
 {
     // per (row half, plane): un-rotate, fold the sign of alpha into the bits, |alpha| pair
     uint32_t abs_pair[2][Q][SUB];
@@ -302,7 +302,11 @@ __device__ __forceinline__ void compute_folded(TileRegs<Q, Z, SUB> &cur, const u
             }
 #pragma unroll
         for (int n = 0; n < 4; ++n) {
-            const f16x8 bx = *reinterpret_cast<const f16x8 *>(xb + (4 * dq + n) * 16);
+            // the expanded operands of a step serve every group of 16 batch columns
+            f16x8 bx[NB];
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+                bx[nb] = *reinterpret_cast<const f16x8 *>(xb + nb * kXBufBytes + (4 * dq + n) * 16);
 #pragma unroll
             for (int t = 0; t < 2; ++t) {
 #pragma unroll
@@ -312,11 +316,16 @@ __device__ __forceinline__ void compute_folded(TileRegs<Q, Z, SUB> &cur, const u
                     if (n == 1) a = expand_byte<1>(w[t][i], w4[t][i], abs_pair[t][i][g]);
                     if (n == 2) a = expand_byte<2>(w[t][i], w4[t][i], abs_pair[t][i][g]);
                     if (n == 3) a = expand_byte<3>(w[t][i], w4[t][i], abs_pair[t][i][g]);
-                    acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, bx, acc[t], 0, 0, 0);
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb)
+                        acc[nb][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, bx[nb], acc[nb][t], 0, 0, 0);
                 }
                 if (Z) {
                     const u32x4 zz = {z_pair[t][g], z_pair[t][g], z_pair[t][g], z_pair[t][g]};
-                    acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, zz), bx, acc[t], 0, 0, 0);
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb)
+                        acc[nb][t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, zz), bx[nb], acc[nb][t],
+                                                                            0, 0, 0);
                 }
             }
         }
@@ -455,14 +464,13 @@ __device__ __forceinline__ void compute_table(const TileRegs<Q, Z, 1> &cur, cons
 // ---------------------------------------------------------------------------------
 // the kernel
 // ---------------------------------------------------------------------------------
-// NB = groups of 16 batch columns (1, 2 or 4; more than one only with VER 2).  With one group the
+// NB = groups of 16 batch columns (1, 2 or 4; with VER 1 or VER 2).  With one group the
 // X slice is double-buffered in LDS; with more, the staged slice (16.6 KB per group) is single-
 // buffered: the next slice waits in registers and replaces it between two barriers.
 template <int Q, int Z, int SUB, int VER, int LDS_STEPS, int NB>
 __global__ __launch_bounds__(256) void bcq_skinny_kernel(SkinnyParams p)
 {
     static_assert(VER == 1 || SUB == 1, "the table kernel needs one scaling group per block");
-    static_assert(NB == 1 || VER == 2, "several batch groups only with the table kernel");
     constexpr bool kDouble = NB == 1;
     constexpr int kBuf = NB * kXBufBytes;
     __shared__ __attribute__((aligned(16))) uint8_t xs[(kDouble ? 2 : 1) * kBuf];
@@ -523,7 +531,7 @@ __global__ __launch_bounds__(256) void bcq_skinny_kernel(SkinnyParams p)
             x_slice_load<NB>(p, xrsrc, n_slice, more, tid, xr);
 
             if (active) {
-                if constexpr (VER == 1) compute_folded<Q, Z, SUB>(cur, xs + buf * kBuf, r, h, acc[0]);
+                if constexpr (VER == 1) compute_folded<Q, Z, SUB, NB>(cur, xs + buf * kBuf, r, h, acc);
                 else compute_table<Q, Z, LDS_STEPS, NB>(cur, xs + buf * kBuf, my_tab, r, h, acc);
             }
             if (!kDouble) __syncthreads();  // everyone done reading the slice that is about to be replaced
@@ -594,8 +602,16 @@ static hipError_t launch_skinny_qz(const SkinnyParams &p, int nb, int parts, boo
 {
     if (sub == 2) return launch_skinny_one<Q, Z, 2, 1, 0, 1>(p, parts, single_slice, stream);
     if (sub == 4) return launch_skinny_one<Q, Z, 4, 1, 0, 1>(p, parts, single_slice, stream);
-    if (version == 1) return launch_skinny_one<Q, Z, 1, 1, 0, 1>(p, parts, single_slice, stream);
-    if constexpr (Q <= 3) {  // with four planes, four column groups do not fit the register file
+    // More than 16 columns: the kernel that folds alpha into A wins (measured 64 / 112 us against
+    // 73 / 124 us for 32 / 64 columns on 7168 x 28672, q = 3): its expansion is shared by the column
+    // groups like the table kernel's, and it needs no per-block accumulators.  Up to 16 columns the
+    // table kernel is a little faster (47.6 against 49.4 us).
+    if (version == 1 || (version == 0 && nb > 1)) {
+        if (nb == 4) return launch_skinny_one<Q, Z, 1, 1, 0, 4>(p, parts, single_slice, stream);
+        if (nb == 2) return launch_skinny_one<Q, Z, 1, 1, 0, 2>(p, parts, single_slice, stream);
+        return launch_skinny_one<Q, Z, 1, 1, 0, 1>(p, parts, single_slice, stream);
+    }
+    if constexpr (Q <= 3) {  // with four planes, four column groups do not fit the table kernel's register budget
         if (nb == 4) return launch_skinny_one<Q, Z, 1, 2, 4, 4>(p, parts, single_slice, stream);
     }
     if (nb == 2) return launch_skinny_one<Q, Z, 1, 2, 4, 2>(p, parts, single_slice, stream);
@@ -621,11 +637,10 @@ hipError_t launch_skinny(const Geom &g, const void *packed, const uint16_t *X, i
     const int parts = tuning.skinny_parts > 0 ? tuning.skinny_parts : -tuning.workgroups;
     const bool single = workspace == nullptr;  // only reachable for a single column slice
     const int sub = g.sub, ver = tuning.skinny_version, steps = tuning.skinny_lds_steps;
-    // Up to 64 batch columns in one pass over the weights with the table kernel (the +-1 operands are
-    // shared by the groups of 16 columns); the kernel that folds alpha into A handles 16 columns per
-    // launch, so wider batches take one pass per 16 columns there.
-    const bool wide_ok = sub == 1 && ver != 1;
-    const int widest = g.q <= 3 ? 64 : 32;
+    // Up to 64 batch columns in one pass over the weights (the expanded operands are shared by the
+    // groups of 16 columns); with several scaling groups per block one pass per 16 columns.
+    const bool wide_ok = sub == 1;
+    const int widest = (g.q <= 3 || ver != 2) ? 64 : 32;
     const int cols_per_launch = wide_ok ? (batch > 32 ? widest : batch > 16 ? 32 : 16) : 16;
     for (int col0 = 0; col0 < batch; col0 += cols_per_launch) {
         const int cols = batch - col0 < cols_per_launch ? batch - col0 : cols_per_launch;

@@ -301,12 +301,18 @@ def test_graph_replay_matches_eager():
         torch.cuda.synchronize()
 
 
+@pytest.mark.parametrize("version", [0, 2])
 @pytest.mark.parametrize("batch", [17, 24, 32, 33, 50, 64])
 @pytest.mark.parametrize("q,offset,group", [(3, False, 128), (2, True, 128), (4, True, 256), (3, True, 64)])
-def test_wide_batches(batch, q, offset, group):
-    """17..64 activation vectors: the table kernel shares the expanded operands between groups of 16
-    columns (q <= 3: up to 64 per pass, q = 4: 32); groups of 64 columns take one pass per 16."""
-    _run_case(203, 2560, q, group, offset, batch=batch, seed=batch + q)
+def test_wide_batches(batch, q, offset, group, version):
+    """17..64 activation vectors: the expanded operands are shared between groups of 16 columns, up to 64
+    per pass (default: the kernel that folds alpha into A; version 2: the table kernel, q = 4: 32 per
+    pass); groups of 64 columns take one pass per 16."""
+    try:
+        bcq.set_option("skinny_version", version)
+        _run_case(203, 2560, q, group, offset, batch=batch, seed=batch + q)
+    finally:
+        bcq.set_option("skinny_version", 0)
 
 
 def test_wide_batch_exact_and_strided():
