@@ -238,7 +238,7 @@ bcq_status bcq_read_probe(const void *buf, size_t bytes, void *sink, void *strea
 /*
  * Launch-shape overrides for tuning runs (HOST state, process-wide, not
  * thread-safe).  Names: "workgroups" (grid size of the GEMV and of the skinny kernel), "waves"
- * (waves per workgroup, 4 or 8), "skinny_parts" (K split of bcq_gemm_skinny for
+ * (waves per workgroup, 4 or 8: the GEMV, and the table kernel of bcq_gemm_skinny up to 16 columns), "skinny_parts" (K split of bcq_gemm_skinny for
  * batch >= 2), "skinny_version" (1 = the kernel that folds alpha into the
  * matrix-core operand, 2 = the kernel that takes +-1 operands from an LDS table;
  * groups of 32/64 always use 1), "skinny_lds_steps" (3 or 4, kernel 2 only);

@@ -8,9 +8,9 @@
 // is the same for every batch up to 16; wider batches (up to 64) reuse the expanded operands for
 // every group of 16 columns.
 //
-// Common skeleton (bcq_skinny_kernel<Q, Z, SUB, VER, LDS_STEPS, NB>):
+// Common skeleton (bcq_skinny_kernel<Q, Z, SUB, VER, LDS_STEPS, NB, NW>):
 //  * Same packed blob as the GEMV (bcq_layout.h).  A work unit is (tile group, column slice): the
-//    four waves of a workgroup take the four row tiles of the group and share an LDS copy of the
+//    NW (4 or 8) waves of a workgroup take the NW row tiles of the group and share an LDS copy of the
 //    slice of X (pitch 1040 B: conflict-free ds_read_b128; double-buffered, one barrier per unit).
 //    The units, ordered tile group first, are cut into equal contiguous ranges, one per workgroup,
 //    with as many workgroups as the chip holds at once: every workgroup does the same number of
@@ -67,13 +67,13 @@ constexpr int kXBufBytes = 16 * kXPitchBytes;
 // through a buffer descriptor covering its batch rows; chunks that do not exist (batch column or
 // column out of range, or no such slice: `wanted` false) are given an out-of-range offset and
 // come back as zeros, so the loads are unconditional.
-template <int NB>
+template <int NB, int NT>
 __device__ __forceinline__ void x_slice_load(const SkinnyParams &p, __amdgpu_buffer_rsrc_t xrsrc, int slice, bool wanted,
-                                             int tid, u32x4 (&xr)[4 * NB])
+                                             int tid, u32x4 (&xr)[1024 * NB / NT])
 {
 #pragma unroll
-    for (int k = 0; k < 4 * NB; ++k) {
-        const int idx = tid + 256 * k, chunk = idx & 63, c = idx >> 6;
+    for (int k = 0; k < 1024 * NB / NT; ++k) {
+        const int idx = tid + NT * k, chunk = idx & 63, c = idx >> 6;
         const int col = slice * kTileCols + kChunkCols * chunk;
         const bool ok = wanted && c < p.batch && col < p.N;
         const uint32_t off = ok ? 2u * ((uint32_t)c * (uint32_t)p.ldx + (uint32_t)col) : 0xfffffff0u;
@@ -95,12 +95,12 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t tile_descriptor(const uint8_t 
 }
 
 // Stores them to LDS, elements reordered to (0,4,1,5,2,6,3,7) within a chunk.
-template <int NB>
-__device__ __forceinline__ void x_slice_store(uint8_t *xs, int tid, const u32x4 (&xr)[4 * NB])
+template <int NB, int NT>
+__device__ __forceinline__ void x_slice_store(uint8_t *xs, int tid, const u32x4 (&xr)[1024 * NB / NT])
 {
 #pragma unroll
-    for (int k = 0; k < 4 * NB; ++k) {
-        const int idx = tid + 256 * k, chunk = idx & 63, c = idx >> 6;
+    for (int k = 0; k < 1024 * NB / NT; ++k) {
+        const int idx = tid + NT * k, chunk = idx & 63, c = idx >> 6;
         const u32x4 v = xr[k];
         u32x4 o;
         o.x = __builtin_amdgcn_perm(v.z, v.x, 0x05040100u);  // (x0, x4)
@@ -340,11 +340,12 @@ constexpr int kTabBytes = 256 * kTabCopies * 16;  // 32 KB
 
 // Sign table: entry b holds 8 binary16 values, pair d = (bit d, bit d + 4) of b, +1.0 for a set bit
 // (the element order the staged X uses); copy c of entry b sits at (8 b + c) * 16.
+template <int NT>
 __device__ __forceinline__ void build_sign_table(uint8_t *tab, int tid)
 {
 #pragma unroll
-    for (int k = 0; k < 8; ++k) {
-        const int idx = tid + 256 * k, b = idx >> 3;
+    for (int k = 0; k < 2048 / NT; ++k) {
+        const int idx = tid + NT * k, b = idx >> 3;
         u32x4 e;
 #pragma unroll
         for (int d = 0; d < 4; ++d)
@@ -467,15 +468,16 @@ __device__ __forceinline__ void compute_table(const TileRegs<Q, Z, 1> &cur, cons
 // NB = groups of 16 batch columns (1, 2 or 4; with VER 1 or VER 2).  With one group the
 // X slice is double-buffered in LDS; with more, the staged slice (16.6 KB per group) is single-
 // buffered: the next slice waits in registers and replaces it between two barriers.
-template <int Q, int Z, int SUB, int VER, int LDS_STEPS, int NB>
-__global__ __launch_bounds__(256) void bcq_skinny_kernel(SkinnyParams p)
+template <int Q, int Z, int SUB, int VER, int LDS_STEPS, int NB, int NW>
+__global__ __launch_bounds__(64 * NW) void bcq_skinny_kernel(SkinnyParams p)
 {
+    constexpr int NT = 64 * NW;
     static_assert(VER == 1 || SUB == 1, "the table kernel needs one scaling group per block");
-    constexpr bool kDouble = NB == 1;
+    constexpr bool kDouble = NB == 1 && NW == 4;
     constexpr int kBuf = NB * kXBufBytes;
     __shared__ __attribute__((aligned(16))) uint8_t xs[(kDouble ? 2 : 1) * kBuf];
     __shared__ __attribute__((aligned(16))) uint8_t tab[VER == 2 ? kTabBytes : 16];
-    __shared__ float stage[4 * kStageFloats];
+    __shared__ float stage[NW * kStageFloats];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: tile pointers stay in SGPRs
@@ -485,7 +487,7 @@ __global__ __launch_bounds__(256) void bcq_skinny_kernel(SkinnyParams p)
     if (u_begin >= u_end) return;  // uniform for the workgroup, before any barrier
 
     int tg = u_begin / p.nslice, slice = u_begin - tg * p.nslice;
-    int tile = 4 * tg + wave;
+    int tile = NW * tg + wave;
     bool active = tile < p.ntile;
 
     const __amdgpu_buffer_rsrc_t xrsrc = x_descriptor(p);
@@ -494,11 +496,11 @@ __global__ __launch_bounds__(256) void bcq_skinny_kernel(SkinnyParams p)
         cur, tile_descriptor(p.blob + ((size_t)slice * p.ntile + (active ? tile : 0)) * p.tile_bytes, p.tile_bytes, active),
         lane, lane & p.scale_lane_mask);
     {
-        u32x4 xr[4 * NB];
-        x_slice_load<NB>(p, xrsrc, slice, true, tid, xr);
-        x_slice_store<NB>(xs, tid, xr);
+        u32x4 xr[1024 * NB / NT];
+        x_slice_load<NB, NT>(p, xrsrc, slice, true, tid, xr);
+        x_slice_store<NB, NT>(xs, tid, xr);
     }
-    if (VER == 2) build_sign_table(tab, tid);
+    if (VER == 2) build_sign_table<NT>(tab, tid);
     __syncthreads();
     const uint8_t *my_tab = tab + (lane & (kTabCopies - 1)) * 16;
 
@@ -517,18 +519,18 @@ __global__ __launch_bounds__(256) void bcq_skinny_kernel(SkinnyParams p)
             const bool more = u + 1 < u_end;
             int n_slice = slice + 1, n_tg = tg;
             if (n_slice == p.nslice) { n_slice = 0; n_tg = tg + 1; }
-            const int n_tile = 4 * n_tg + wave;
+            const int n_tile = NW * n_tg + wave;
             const bool n_active = more && n_tile < p.ntile;
             // unconditional requests for it (empty descriptor / out-of-range offsets when there is
             // none): they stay in flight while this unit is computed
             TileRegs<Q, Z, SUB> nxt;
-            u32x4 xr[4 * NB];
+            u32x4 xr[1024 * NB / NT];
             load_tile_buf<Q, Z, SUB>(
                 nxt,
                 tile_descriptor(p.blob + ((size_t)n_slice * p.ntile + (n_active ? n_tile : 0)) * p.tile_bytes,
                                 p.tile_bytes, n_active),
                 lane, lane & p.scale_lane_mask);
-            x_slice_load<NB>(p, xrsrc, n_slice, more, tid, xr);
+            x_slice_load<NB, NT>(p, xrsrc, n_slice, more, tid, xr);
 
             if (active) {
                 if constexpr (VER == 1) compute_folded<Q, Z, SUB, NB>(cur, xs + buf * kBuf, r, h, acc);
@@ -536,7 +538,7 @@ __global__ __launch_bounds__(256) void bcq_skinny_kernel(SkinnyParams p)
             }
             if (!kDouble) __syncthreads();  // everyone done reading the slice that is about to be replaced
             if (more) {
-                x_slice_store<NB>(xs + (kDouble ? (buf ^ 1) * kBuf : 0), tid, xr);
+                x_slice_store<NB, NT>(xs + (kDouble ? (buf ^ 1) * kBuf : 0), tid, xr);
                 cur = nxt;
             }
             tg = n_tg; slice = n_slice; tile = n_tile; active = n_active;
@@ -562,13 +564,13 @@ __global__ __launch_bounds__(256) void bcq_skinny_kernel(SkinnyParams p)
 // host side
 // ---------------------------------------------------------------------------------
 // Number of workgroups of a kernel the current device holds at once (asked once per kernel).
-template <int Q, int Z, int SUB, int VER, int LDS_STEPS, int NB>
+template <int Q, int Z, int SUB, int VER, int LDS_STEPS, int NB, int NW>
 static int resident_groups()
 {
     static int cached = 0;
     if (cached == 0) {
         int per_cu = 0, dev = 0, cus = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, bcq_skinny_kernel<Q, Z, SUB, VER, LDS_STEPS, NB>, 256,
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, bcq_skinny_kernel<Q, Z, SUB, VER, LDS_STEPS, NB, NW>, 64 * NW,
                                                          0) != hipSuccess ||
             per_cu < 1)
             per_cu = 1;
@@ -582,23 +584,27 @@ static int resident_groups()
 
 // Grid size: `parts` > 0: that many workgroups per tile group (a K split); `parts` < 0: -parts
 // workgroups; 0: as many workgroups as are resident.
-template <int Q, int Z, int SUB, int VER, int LDS_STEPS, int NB>
-static hipError_t launch_skinny_one(const SkinnyParams &p, int parts, bool single_slice, hipStream_t stream)
+template <int Q, int Z, int SUB, int VER, int LDS_STEPS, int NB, int NW = 4>
+static hipError_t launch_skinny_one(SkinnyParams p, int parts, bool single_slice, hipStream_t stream)
 {
+    p.ntg = (p.ntile + NW - 1) / NW;  // the NW waves of a workgroup take the NW row tiles of a tile group
+    const long long units = (long long)p.ntg * p.nslice;
+    if (units > 0x7fffffffLL) return hipErrorInvalidValue;
+    p.units = (int)units;
     long long groups = parts > 0 ? (long long)parts * p.ntg
-                                 : parts < 0 ? -(long long)parts : resident_groups<Q, Z, SUB, VER, LDS_STEPS, NB>();
+                                 : parts < 0 ? -(long long)parts : resident_groups<Q, Z, SUB, VER, LDS_STEPS, NB, NW>();
     if (groups > p.units) groups = p.units;
     if (single_slice) groups = p.ntg;  // no workspace: one unit per tile group, nothing to combine
     if (groups < 1) groups = 1;
-    hipLaunchKernelGGL((bcq_skinny_kernel<Q, Z, SUB, VER, LDS_STEPS, NB>), dim3((unsigned)groups), dim3(256), 0, stream,
-                       p);
+    hipLaunchKernelGGL((bcq_skinny_kernel<Q, Z, SUB, VER, LDS_STEPS, NB, NW>), dim3((unsigned)groups), dim3(64 * NW), 0,
+                       stream, p);
     return hipGetLastError();
 }
 
 // One launch for up to 16 NB batch columns; p.X / p.Y / p.accum / p.batch describe exactly those.
 template <int Q, int Z>
 static hipError_t launch_skinny_qz(const SkinnyParams &p, int nb, int parts, bool single_slice, int sub, int version,
-                                   int lds_steps, hipStream_t stream)
+                                   int lds_steps, int waves, hipStream_t stream)
 {
     if (sub == 2) return launch_skinny_one<Q, Z, 2, 1, 0, 1>(p, parts, single_slice, stream);
     if (sub == 4) return launch_skinny_one<Q, Z, 4, 1, 0, 1>(p, parts, single_slice, stream);
@@ -617,6 +623,10 @@ static hipError_t launch_skinny_qz(const SkinnyParams &p, int nb, int parts, boo
     if (nb == 2) return launch_skinny_one<Q, Z, 1, 2, 4, 2>(p, parts, single_slice, stream);
     // all four MFMA steps of a block from the LDS table measured fastest; 3 (one step expanded in
     // registers) is kept as the alternative for tuning runs
+    // Eight waves per workgroup (eight row tiles share one staged slice of X, single-buffered) pay off
+    // on the large layers: 42.5 against 48.0 us on 7168 x 28672, nothing on 9216 x 9216, a loss below.
+    const bool eight = waves == 8 || (waves == 0 && (long long)p.ntile * p.nslice >= 8192);
+    if (eight && lds_steps != 3) return launch_skinny_one<Q, Z, 1, 2, 4, 1, 8>(p, parts, single_slice, stream);
     return lds_steps == 3 ? launch_skinny_one<Q, Z, 1, 2, 3, 1>(p, parts, single_slice, stream)
                           : launch_skinny_one<Q, Z, 1, 2, 4, 1>(p, parts, single_slice, stream);
 }
@@ -627,10 +637,7 @@ hipError_t launch_skinny(const Geom &g, const void *packed, const uint16_t *X, i
     SkinnyParams p;
     p.blob = static_cast<const uint8_t *>(packed);
     p.M = g.M; p.N = g.N; p.Mp = g.Mp; p.ldx = ldx; p.ldy = ldy;
-    p.ntile = g.ntile; p.nslice = g.nslice; p.ntg = (g.ntile + 3) / 4;
-    const long long units = (long long)p.ntg * g.nslice;
-    if (units > 0x7fffffffLL) return hipErrorInvalidValue;
-    p.units = (int)units;
+    p.ntile = g.ntile; p.nslice = g.nslice; p.ntg = 0; p.units = 0;  // set per kernel (waves per workgroup)
     p.tile_bytes = g.tile_bytes;
     p.scale_lane_mask = g.scale_lanes - 1;
     // forced grid sizes (tuning runs, tests): a K split per tile group, or a plain number of workgroups
@@ -651,14 +658,14 @@ hipError_t launch_skinny(const Geom &g, const void *packed, const uint16_t *X, i
         const int nb = cols > 32 ? 4 : cols > 16 ? 2 : 1;
         hipError_t e = hipErrorInvalidValue;
         switch (g.q * 2 + g.z) {
-            case 2: e = launch_skinny_qz<1, 0>(p, nb, parts, single, sub, ver, steps, stream); break;
-            case 3: e = launch_skinny_qz<1, 1>(p, nb, parts, single, sub, ver, steps, stream); break;
-            case 4: e = launch_skinny_qz<2, 0>(p, nb, parts, single, sub, ver, steps, stream); break;
-            case 5: e = launch_skinny_qz<2, 1>(p, nb, parts, single, sub, ver, steps, stream); break;
-            case 6: e = launch_skinny_qz<3, 0>(p, nb, parts, single, sub, ver, steps, stream); break;
-            case 7: e = launch_skinny_qz<3, 1>(p, nb, parts, single, sub, ver, steps, stream); break;
-            case 8: e = launch_skinny_qz<4, 0>(p, nb, parts, single, sub, ver, steps, stream); break;
-            case 9: e = launch_skinny_qz<4, 1>(p, nb, parts, single, sub, ver, steps, stream); break;
+            case 2: e = launch_skinny_qz<1, 0>(p, nb, parts, single, sub, ver, steps, tuning.waves, stream); break;
+            case 3: e = launch_skinny_qz<1, 1>(p, nb, parts, single, sub, ver, steps, tuning.waves, stream); break;
+            case 4: e = launch_skinny_qz<2, 0>(p, nb, parts, single, sub, ver, steps, tuning.waves, stream); break;
+            case 5: e = launch_skinny_qz<2, 1>(p, nb, parts, single, sub, ver, steps, tuning.waves, stream); break;
+            case 6: e = launch_skinny_qz<3, 0>(p, nb, parts, single, sub, ver, steps, tuning.waves, stream); break;
+            case 7: e = launch_skinny_qz<3, 1>(p, nb, parts, single, sub, ver, steps, tuning.waves, stream); break;
+            case 8: e = launch_skinny_qz<4, 0>(p, nb, parts, single, sub, ver, steps, tuning.waves, stream); break;
+            case 9: e = launch_skinny_qz<4, 1>(p, nb, parts, single, sub, ver, steps, tuning.waves, stream); break;
         }
         if (e != hipSuccess) return e;
     }

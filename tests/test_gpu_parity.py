@@ -247,6 +247,27 @@ def test_skinny_kernel_variants(option, value, q, offset):
         bcq.set_option(option, 0)
 
 
+@pytest.mark.parametrize("workgroups", [0, 1, 3, 10, 23])
+@pytest.mark.parametrize("q,offset", [(3, True), (1, False), (4, True), (2, False)])
+def test_skinny_eight_waves_per_workgroup(workgroups, q, offset):
+    """The table kernel with eight waves (eight row tiles) per workgroup, which large layers use: forced
+    here on small ragged shapes (10 row tiles = 2 tile groups, the second mostly empty; 3 row tiles;
+    M % 32 != 0), any work split, bit-exact on exact inputs, workspace left zero."""
+    try:
+        bcq.set_option("waves", 8)
+        bcq.set_option("workgroups", workgroups)
+        L = bcq_synth.make_exact_layer(300, 5120, q, group=128, offset=offset, batch=6, seed=31 + q)
+        pl = U.upload_and_pack(L, max_batch=6)
+        expect = ref.gemm(L.planes, L.alpha, L.offset, L.x).astype(np.float16).astype(np.float64)
+        assert np.array_equal(U.gpu_gemm(pl, U.x_dev(L)).astype(np.float64), expect)
+        assert not pl.workspace.cpu().numpy().any()
+        _run_case(203, 3200, q, 128, offset, batch=13, seed=q + workgroups)
+        _run_case(70, 1536, q, 256, offset, batch=2, seed=q + workgroups + 1)
+    finally:
+        bcq.set_option("workgroups", 0)
+        bcq.set_option("waves", 0)
+
+
 @pytest.mark.parametrize("workgroups", [1, 4, 7, 11, 29])
 @pytest.mark.parametrize("version", [1, 2])
 def test_skinny_work_split_does_not_change_results(workgroups, version):
