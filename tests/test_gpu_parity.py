@@ -263,6 +263,7 @@ def test_skinny_eight_waves_per_workgroup(workgroups, q, offset):
         assert not pl.workspace.cpu().numpy().any()
         _run_case(203, 3200, q, 128, offset, batch=13, seed=q + workgroups)
         _run_case(70, 1536, q, 256, offset, batch=2, seed=q + workgroups + 1)
+        _run_case(203, 3200, q, 128, offset, batch=29, seed=q + workgroups + 2)   # 32 columns per pass, eight waves
     finally:
         bcq.set_option("workgroups", 0)
         bcq.set_option("waves", 0)
