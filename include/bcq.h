@@ -213,9 +213,9 @@ bcq_status bcq_gemv(const bcq_desc *desc, const void *packed, const uint16_t *x,
                     uint16_t *y, void *workspace, void *stream);
 
 /*
- * Y[j][m] = sum_k W_q[m][k] X[j][k],  1 <= batch <= BCQ_MAX_BATCH.  The weights are read once
- * per call for batch <= 64 with groups that are multiples of 128 (q <= 3; q = 4: once per 32
- * columns), and once per 16 batch columns for groups of 32/64.
+ * Y[j][m] = sum_k W_q[m][k] X[j][k],  1 <= batch <= BCQ_MAX_BATCH (64).  The weights are read once
+ * per call with groups that are multiples of 128 (or N), and once per 16 batch columns with
+ * groups of 32/64.
  *   X   DEVICE, row j starts at X + j*ldx (elements), ldx >= N, ldx % 8 == 0
  *   Y   DEVICE, row j starts at Y + j*ldy (elements), ldy >= M
  *   workspace as for bcq_gemv with bcq_workspace_bytes(desc, batch)
@@ -237,12 +237,14 @@ bcq_status bcq_read_probe(const void *buf, size_t bytes, void *sink, void *strea
 
 /*
  * Launch-shape overrides for tuning runs (HOST state, process-wide, not
- * thread-safe).  Names: "workgroups" (grid size of the GEMV and of the skinny kernel), "waves"
- * (waves per workgroup, 4 or 8: the GEMV, and the table kernel of bcq_gemm_skinny up to 16 columns), "skinny_parts" (K split of bcq_gemm_skinny for
- * batch >= 2), "skinny_version" (1 = the kernel that folds alpha into the
- * matrix-core operand, 2 = the kernel that takes +-1 operands from an LDS table;
- * groups of 32/64 always use 1), "skinny_lds_steps" (3 or 4, kernel 2 only);
- * 0 = automatic.
+ * thread-safe).  Names: "workgroups" (grid size of the GEMV and of the skinny
+ * kernel), "waves" (waves per workgroup, 4 or 8: the GEMV, the table kernel of
+ * bcq_gemm_skinny up to 16 columns and its 32-column pass), "skinny_parts" (K
+ * split of bcq_gemm_skinny for batch >= 2), "skinny_version" (1 = the kernel
+ * that folds alpha into the matrix-core operand, 2 = the kernel that takes +-1
+ * operands from an LDS table, with q = 4 at most 32 columns per pass; groups of
+ * 32/64 always use 1), "skinny_lds_steps" (3 or 4, kernel 2 only); 0 =
+ * automatic.
  * Unknown names or values return BCQ_ERR_INVALID_ARG.
  */
 bcq_status bcq_set_option(const char *name, int32_t value);
