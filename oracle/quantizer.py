@@ -110,6 +110,30 @@ def gptq(W, H, S, qbias, choices, n, damp=0.01):
     return Wq
 
 
+def gptq_follow(W, U, S, qbias, choices, n, follow):
+    """The pass of gptq() with a given factor U (upper triangular, H^-1 = U^T U), replayed against the
+    integers `follow` [M][N] of a second implementation: at every column the oracle takes its own
+    decision (Eq. 5 step 1, Eq. 6) from its own binary64 working weight; where `follow` differs, the
+    event is recorded and `follow`'s integer is taken instead, so that the compensation of Eq. 2 for the
+    later columns follows the implementation under test.  Returns the list of such events as
+    (m, j, t, own, taken) with t = (w - qbias) / S, the working weight in quantisation steps at that
+    moment.  A parity test then shows that every event is a near-tie of the rounding of t (and that
+    `taken` is what the other side of the tie gives); with an empty list `follow` equals gptq()'s result."""
+    W = np.array(W, dtype=np.float64)
+    U = np.asarray(U, dtype=np.float64)
+    M, N = W.shape
+    events = []
+    for j in range(N):
+        for m in range(M):
+            own = int(quant_row(W[m, j:j + 1], S[m], qbias[m], choices[m], n)[0])
+            wq = int(follow[m, j])
+            if wq != own:
+                events.append((m, j, float((W[m, j] - qbias[m]) / S[m]), own, wq))
+            err = (W[m, j] - (S[m] * wq + qbias[m])) / U[j, j]
+            W[m, j:] -= err * U[j, j:]
+    return events
+
+
 def cholesky_factor(H, damp=0.01):
     """U of gptq(): upper Cholesky factor of (H + damp * mean(diag H) I)^-1."""
     H = np.array(H, dtype=np.float64)

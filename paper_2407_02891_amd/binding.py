@@ -232,6 +232,10 @@ class PackedLayer:
     def gemm_skinny(self, X, Y=None):
         import torch
         batch = X.shape[0]
+        if not 1 <= batch <= BCQ_MAX_BATCH:
+            raise BcqError(BCQ_ERR_INVALID_ARG, "PackedLayer.gemm_skinny (batch outside 1..%d)" % BCQ_MAX_BATCH)
+        if batch > self.max_batch:   # the workspace holds max_batch accumulators per row
+            raise BcqError(BCQ_ERR_WORKSPACE, "PackedLayer.gemm_skinny (batch %d > max_batch %d)" % (batch, self.max_batch))
         if Y is None:
             Y = torch.empty((batch, self.desc.M), dtype=torch.float16, device=self.device)
         gemm_skinny(self.desc, self.packed, X, X.stride(0), Y, Y.stride(0), batch,

@@ -33,30 +33,69 @@ def test_opt30b_q3(M, N):
     _check(M, N, 3, False)
 
 
-@pytest.mark.parametrize("M,N", [(7168, 7168), (7168, 28672)])
+@pytest.mark.parametrize("M,N", [(7168, 7168), (28672, 7168), (7168, 28672)])
 def test_opt30b_q2_offset(M, N):
     """configs[2], batch 1"""
     _check(M, N, 2, True)
 
 
-def test_opt66b_q3_outliers():
-    """configs[3], batch 1, the widest layer"""
-    _check(9216, 36864, 3, False, outlier_frac=0.01)
+@pytest.mark.parametrize("M,N", [(9216, 9216), (36864, 9216), (9216, 36864)])
+def test_opt66b_q3_outliers(M, N):
+    """configs[3], batch 1"""
+    _check(M, N, 3, False, outlier_frac=0.01)
 
 
-@pytest.mark.parametrize("M,N,q", [(1024, 8192, 3), (8192, 28672, 2)])
+@pytest.mark.parametrize("q", [2, 3])
+@pytest.mark.parametrize("M,N", [(8192, 8192), (1024, 8192), (28672, 8192), (8192, 28672)])
 def test_llama70b_shapes(M, N, q):
-    """configs[4]: GQA k/v projection and the down projection"""
+    """configs[4], each distinct shape on its own: q/o, k/v (GQA), gate/up, down; q = 2 and 3"""
     _check(M, N, q, False)
 
 
-@pytest.mark.parametrize("M,N,q,offset,batch", [(7168, 7168, 2, True, 8), (9216, 9216, 3, False, 4),
-                                                  (9216, 9216, 3, False, 16), (28672, 7168, 2, True, 8),
-                                                  (36864, 9216, 3, False, 16), (7168, 28672, 3, False, 64)])
+@pytest.mark.parametrize("M,N,q,offset,batch", [(7168, 7168, 2, True, 8), (28672, 7168, 2, True, 8),
+                                                  (7168, 28672, 2, True, 8),
+                                                  (9216, 9216, 3, False, 4), (9216, 9216, 3, False, 16),
+                                                  (36864, 9216, 3, False, 4), (36864, 9216, 3, False, 16),
+                                                  (9216, 36864, 3, False, 4), (9216, 36864, 3, False, 16),
+                                                  (7168, 28672, 3, False, 64)])
 def test_skinny_fullsize(M, N, q, offset, batch):
-    """configs[2] (q=2 with offset, batch 8), configs[3] (batch 4 and 16, outlier channels, incl. the tallest
-    layer) and the dominant layer of configs[1] at the widest batch of one pass (64)"""
-    _check(M, N, q, offset, batch=batch, outlier_frac=0.01 if N == 9216 else 0.0)
+    """configs[2] (q=2 with offset, batch 8, all three layers), configs[3] (batch 4 and 16, outlier channels,
+    all three layers) and the dominant layer of configs[1] at the widest batch of one pass (64)"""
+    _check(M, N, q, offset, batch=batch, outlier_frac=0.01 if 9216 in (M, N) else 0.0)
+
+
+@pytest.mark.parametrize("q", [2, 3])
+def test_llama70b_block_in_sequence(q):
+    """configs[4]: the seven GEMVs of the decoder block (q, k, v, o, gate, up, down) enqueued back to back on
+    one stream with ONE shared workspace and no synchronisation in between; every output is then checked
+    on sampled rows.  (The workspace is left zero by each call, which is what lets the next one use it.)"""
+    import torch
+    import paper_2407_02891_amd as bcq
+    layers = []
+    ws_bytes = 0
+    for k, (name, M, N) in enumerate(bcq_synth.LLAMA2_70B_BLOCK):
+        L = bcq_synth.make_layer(M, N, q, group=128, offset=False, seed=k)
+        pl = U.upload_and_pack(L)
+        # keep only what the check needs: the sampled rows' operands and the activations
+        rows = _sample_rows(M, n=64, seed=k)
+        keep = (np.ascontiguousarray(L.planes[:, rows]), np.ascontiguousarray(L.alpha[rows]), L.x.copy())
+        layers.append((name, pl, U.x_dev(L)[0].contiguous(), torch.empty(M, dtype=torch.float16, device="cuda"), rows, keep))
+        ws_bytes = max(ws_bytes, pl.workspace_bytes)
+        del L
+    shared = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    bcq.workspace_init(shared)
+    torch.cuda.synchronize()
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        for rep in range(2):                      # twice: the second pass starts from what the first left behind
+            for name, pl, x, y, rows, keep in layers:
+                bcq.gemv(pl.desc, pl.packed, x, y, shared)
+    stream.synchronize()
+    torch.cuda.synchronize()
+    from oracle import ref
+    for name, pl, x, y, rows, (planes, alpha, xh) in layers:
+        U.gate(y.cpu().numpy()[None, rows], ref.gemm(planes, alpha, None, xh), f"block layer {name} q={q}")
+    assert not shared.cpu().numpy().any()
 
 
 def test_llama70b_fused_qkv_equals_three_gemvs():

@@ -118,6 +118,53 @@ def test_subnormal_alpha_and_zero_inputs():
     assert not U.gpu_gemv(pl, xz).view(np.uint16).any()
 
 
+@pytest.mark.parametrize("version", [1, 2])
+@pytest.mark.parametrize("batch", [1, 5, 40])
+@pytest.mark.parametrize("group,offset", [(128, False), (128, True), (64, False)])
+def test_all_subnormal_alpha_is_exact(version, batch, group, offset):
+    """Every alpha (and offset) a binary16 subnormal (k * 2^-24, k = 1..1023), x small integers: each
+    product and every partial sum is a multiple of 2^-24 below 2^24 of them, hence exact in binary32 and
+    binary64 alike, so the result must be the oracle's rounded once to binary16 -- bit for bit.  A path
+    that flushed subnormal scales (in a conversion, or as a matrix-core operand in the kernel that folds
+    alpha into it) would return zeros (sums of offsets only).  Batch 1 is the table GEMV, 5 and 40 the
+    two skinny kernels (groups of 64 always take the alpha-folding one)."""
+    L = bcq_synth.make_exact_layer(150, 2048, 3, group=group, offset=offset, batch=batch, seed=90 + batch)
+    rng = np.random.default_rng(batch + group)
+    L.alpha = rng.integers(1, 1024, size=L.alpha.shape, dtype=np.uint16).view(np.float16)
+    assert np.all(L.alpha.astype(np.float64) < 2.0 ** -14) and np.all(L.alpha.astype(np.float64) > 0)
+    if offset:  # subnormal offsets of either sign, so that the scales are not drowned by the offset term
+        z = rng.integers(1, 1024, size=L.offset.shape, dtype=np.uint16) | (rng.integers(0, 2, size=L.offset.shape, dtype=np.uint16) << 15)
+        L.offset = z.view(np.float16)
+    y_ref = ref.gemm(L.planes, L.alpha, L.offset, L.x)
+    assert np.abs(y_ref).max() > 2.0 ** -12, "the scales must matter"
+    expect = y_ref.astype(np.float16).astype(np.float64)
+    pl = U.upload_and_pack(L, max_batch=batch)
+    try:
+        bcq.set_option("skinny_version", version)
+        Y = U.gpu_gemv(pl, U.x_dev(L))[None, :] if batch == 1 else U.gpu_gemm(pl, U.x_dev(L))
+    finally:
+        bcq.set_option("skinny_version", 0)
+    assert np.array_equal(Y.astype(np.float64), expect), np.abs(Y.astype(np.float64) - expect).max()
+
+
+def test_gemm_skinny_refuses_a_batch_beyond_the_workspace():
+    """PackedLayer sizes its workspace for max_batch; a larger batch must be refused on the host (the kernel
+    would address accumulators past the allocation), as must a batch outside 1..BCQ_MAX_BATCH."""
+    L = bcq_synth.make_layer(64, 1024, 2, group=128, offset=False, batch=4, seed=1)
+    pl = U.upload_and_pack(L, max_batch=2)
+    X = U.x_dev(L)
+    with pytest.raises(bcq.BcqError) as e:
+        pl.gemm_skinny(X)
+    assert e.value.status == bcq.binding.BCQ_ERR_WORKSPACE
+    Y = U.gpu_gemm(pl, X[:2].contiguous())
+    U.gate(Y, ref.gemm(L.planes, L.alpha, None, L.x[:2]))
+    big = torch.zeros((bcq.binding.BCQ_MAX_BATCH + 1, L.N), dtype=torch.float16, device="cuda")
+    with pytest.raises(bcq.BcqError) as e:
+        bcq.PackedLayer(64, 1024, 2, 128, False, max_batch=bcq.binding.BCQ_MAX_BATCH).pack_from(
+            U.to_dev(L.codes()), U.to_dev(L.alpha.view(np.uint16).astype(np.int16)).view(torch.float16), None).gemm_skinny(big)
+    assert e.value.status == bcq.binding.BCQ_ERR_INVALID_ARG
+
+
 @pytest.mark.parametrize("batch", [2, 4, 8, 16])
 def test_skinny_batches(batch):
     _run_case(160, 1536, 3, 128, True, batch=batch, seed=batch)

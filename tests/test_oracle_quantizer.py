@@ -149,3 +149,31 @@ def test_constant_row_is_reproduced():
     choices = [fuse.bcchoice(parts[i], 3) for i in p]
     Wq = Q.gptq(W, H, S, b, choices, 3)
     assert (Wq[1] == 0).all()
+
+
+def test_gptq_follow_replays_gptq_and_reports_forced_columns():
+    """gptq_follow with gptq()'s own integers reports nothing; with one integer replaced it reports
+    exactly that column (with the working weight gptq() had there), and the later columns of that
+    row, re-derived by gptq() from the changed history, are reproduced by following them."""
+    W, X = _layer(6, 24, 60, 7)
+    H = Q.hessian(X)
+    n, q = 3, 2
+    part = fuse.all_partitions(n, q)[1]
+    choice = fuse.bcchoice(part, n)
+    S = (W.max(1) - W.min(1)) / (2 ** n - 1)
+    b = W.min(1)
+    choices = [choice] * W.shape[0]
+    Wq = Q.gptq(W, H, S, b, choices, n)
+    U = Q.cholesky_factor(H)
+    assert Q.gptq_follow(W, U, S, b, choices, n, Wq) == []
+    # force another member of the set at (2, 5); rebuild the rest of the row as the definition would
+    forced = Wq.copy()
+    other = [c for c in choice if c != Wq[2, 5]][0]
+    forced[2, 5] = other
+    w = W[2].astype(np.float64).copy()
+    for j in range(W.shape[1]):
+        wq = forced[2, j] if j <= 5 else Q.quant_row(w[j:j + 1], S[2], b[2], choice, n)[0]
+        forced[2, j] = wq
+        w[j:] -= (w[j] - (S[2] * wq + b[2])) / U[j, j] * U[j, j:]
+    ev = Q.gptq_follow(W, U, S, b, choices, n, forced)
+    assert len(ev) == 1 and ev[0][:2] == (2, 5) and ev[0][3] == Wq[2, 5] and ev[0][4] == other
