@@ -234,20 +234,27 @@ def main():
     read_probe = dict(bytes=nbytes_blob, us=round(probe_us, 3), GBps=round(nbytes_blob / probe_us / 1e3, 1),
                       what="plain streaming read of the dominant layer's packed weights (no arithmetic)")
     achieved = dom["weight_bytes"] / (dom["us_per_gemv"] * 1e-6) / 1e9
+    MFMA_PEAK_TFLOPS = 2500.0  # dense binary16 matrix-core peak
     if B > 1:
-        # The single-pass skinny kernel contracts on the matrix cores (binary16 in, fp32 accumulate):
-        # useful work 2 * q * M * N * batch flop per launch against the dense fp16 MFMA peak.  What
-        # actually limits it is turning every sign into a binary16 operand (LDS table reads), which
-        # costs the same for any batch -- hence the low fraction at small batch.
+        # The single-pass skinny kernel reads the weights once (HBM) and contracts on the matrix cores
+        # (binary16 in, fp32 accumulate; useful work 2 * q * M * N * batch flop per launch).  Both roofs are
+        # evaluated; the one that needs more time at its peak binds, and `frac` is taken against it.
         flop = 2.0 * Q * dom["M"] * dom["N"] * B
-        tfl = flop / (dom["us_per_gemv"] * 1e-6) / 1e12
-        roofline = dict(bound="mfma", kernel="bcq_skinny_kernel (q=%d, %s, %s, batch %d) on %dx%d"
-                                             % (Q, "offset" if args.offset else "no offset",
-                                                "row-wise scales" if args.rowwise else "group 128", B, dom["M"], dom["N"]),
-                        achieved=round(tfl, 2), peak=2500.0, unit="TFLOP/s", frac=round(tfl / 2500.0, 4),
-                        flop_per_launch=flop, us_per_launch=dom["us_per_gemv"], traffic=None,
-                        limiter="LDS read bandwidth of the sign-expansion table",
-                        weight_GBps=dom["weight_GBps"])
+        us = dom["us_per_gemv"]
+        t_hbm_us = dom["weight_bytes"] / (HBM_PEAK_GBS * 1e9) * 1e6
+        t_mfma_us = flop / (MFMA_PEAK_TFLOPS * 1e12) * 1e6
+        tfl = flop / (us * 1e-6) / 1e12
+        hbm = dict(bound="hbm", achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s",
+                   frac=round(achieved / HBM_PEAK_GBS, 4), time_at_peak_us=round(t_hbm_us, 2))
+        mfma = dict(bound="mfma", achieved=round(tfl, 2), peak=MFMA_PEAK_TFLOPS, unit="TFLOP/s",
+                    frac=round(tfl / MFMA_PEAK_TFLOPS, 4), time_at_peak_us=round(t_mfma_us, 2))
+        binding, other = (hbm, mfma) if t_hbm_us >= t_mfma_us else (mfma, hbm)
+        roofline = dict(binding)
+        roofline.update(kernel="bcq_skinny_kernel (q=%d, %s, %s, batch %d) on %dx%d"
+                               % (Q, "offset" if args.offset else "no offset",
+                                  "row-wise scales" if args.rowwise else "group 128", B, dom["M"], dom["N"]),
+                        bytes_per_launch=dom["weight_bytes"], flop_per_launch=flop, us_per_launch=us, traffic=None,
+                        secondary=other)
     else:
         roofline = dict(bound="hbm",
                         kernel="bcq_gemv_kernel (q=%d, %s, %s) on %dx%d"
@@ -256,12 +263,16 @@ def main():
                         achieved=round(achieved, 1), peak=HBM_PEAK_GBS, unit="GB/s",
                         frac=round(achieved / HBM_PEAK_GBS, 4), bytes_per_launch=dom["weight_bytes"],
                         us_per_launch=dom["us_per_gemv"], traffic=None)
-    # HBM bytes per launch measured separately with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE); see profiles/
+    # HBM bytes per launch come from two separate rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) whose summary is
+    # committed under profiles/; this run does not measure them, and the line says so.
     traffic_file = os.path.join(ROOT, "profiles", "bcq_gemv_opt30b_q3_hbm_traffic.md")
     if os.path.exists(traffic_file) and args.workload == "opt30b" and Q == 3 and B == 1 and not args.offset and not args.rowwise:
         for line in open(traffic_file):
             if line.startswith("hbm_bytes_per_launch_fc2"):
                 roofline["traffic"] = float(line.split("=")[1])
+                roofline["traffic_source"] = ("rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE summary in "
+                                              "profiles/bcq_gemv_opt30b_q3_hbm_traffic.md (separate runs of this "
+                                              "command), not measured by this run")
 
     # ---- oracle on the host cores, same layer set --------------------------------------
     cpu = None

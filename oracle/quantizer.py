@@ -72,6 +72,13 @@ def search(W, H, n, q, grid):
     return S_out, b_out, p_out, e_out
 
 
+def eq2_delta(err, Hinv):
+    """Eq. 2: the change of the remaining weights F (first entry: the weight being quantised, which so
+    lands on its quantised value) that compensates quantising it with error err = w_q - quant(w_q);
+    Hinv = H_F^-1."""
+    return -err / Hinv[0, 0] * Hinv[:, 0]
+
+
 def gptq_definition(W, H, S, qbias, choices, n, damp=0.01):
     """GPTQ as Eq. 1-2 state it, with the inverse Hessian of the REMAINING weights recomputed
     from scratch at every column (slow; the definition).  choices[m] = BCchoice of row m.
@@ -87,7 +94,7 @@ def gptq_definition(W, H, S, qbias, choices, n, damp=0.01):
             wq = quant_row(W[m, j:j + 1], S[m], qbias[m], choices[m], n)[0]
             Wq[m, j] = wq
             err = W[m, j] - (S[m] * wq + qbias[m])     # w_q - quant(w_q)
-            W[m, j:] -= err / Hinv[0, 0] * Hinv[:, 0]  # Eq. 2 (its own component becomes quant(w_q))
+            W[m, j:] += eq2_delta(err, Hinv)           # Eq. 2 (its own component becomes quant(w_q))
     return Wq
 
 

@@ -189,7 +189,9 @@ def test_column_probe_fixes_bit_order_and_group_index():
     alpha = np.zeros((M, N // group, q), dtype=np.float16)
     alpha[:, :, 0] = np.arange(1, 5)[None, :]                 # plane 0 scale = group index + 1
     alpha[:, :, 1] = 0.25
-    z = (np.arange(M)[:, None] * 8 + np.arange(N // group)[None, :]).astype(np.float16)
+    # offset = 16 m + 3 grp: its group term must not cancel the plane-0 scale's (a mutation check found that
+    # 8 m + grp did, which left a shifted group index unnoticed by this pin)
+    z = (np.arange(M)[:, None] * 16 + 3 * np.arange(N // group)[None, :]).astype(np.float16)
     for k in (0, 31, 63, 64, k_hot, k_hot + 1, 255):
         x = np.zeros((1, N), dtype=np.float16)
         x[0, k] = 1.0
@@ -197,7 +199,7 @@ def test_column_probe_fixes_bit_order_and_group_index():
         for m in range(M):
             grp = k // group
             s1 = 1.0 if (m == m_hot and k == k_hot) else -1.0
-            want = -(grp + 1) + 0.25 * s1 + (8 * m + grp)
+            want = -(grp + 1) + 0.25 * s1 + (16 * m + 3 * grp)
             assert y[m] == want, (k, m)
 
 

@@ -76,7 +76,7 @@ def test_eq2_is_the_least_squares_compensation():
     target0 = w[0] + 0.37                                       # "quant(w_0)"
     H = Q.hessian(X)
     Hinv = np.linalg.inv(H)
-    delta = -(w[0] - target0) / Hinv[0, 0] * Hinv[:, 0]        # Eq. 2
+    delta = Q.eq2_delta(w[0] - target0, Hinv)                   # the oracle's Eq. 2
     assert np.isclose(w[0] + delta[0], target0)
     # minimise ||d X||^2 with d_0 = target0 - w_0: d_rest = argmin || d_0 X_0 + d_rest X_rest ||
     d0 = target0 - w[0]
