@@ -39,11 +39,15 @@ typedef enum {
     BCQ_ERR_INVALID_ARG = 1, /* NULL pointer, bad size, misalignment, bad batch     */
     BCQ_ERR_UNSUPPORTED = 2, /* well-formed request outside what the kernels cover  */
     BCQ_ERR_WORKSPACE = 3,   /* workspace missing where bcq_workspace_bytes() > 0   */
-    BCQ_ERR_HIP = 4          /* the HIP runtime reported an error at launch         */
+    BCQ_ERR_HIP = 4,         /* the HIP runtime reported an error at launch         */
+    BCQ_ERR_SCRATCH_LIMIT = 5 /* bcq_gemv_noalloc: more rows than BCQ_NOALLOC_MAX_ROWS */
 } bcq_status;
 
 /* Version of the opaque packed layout written by bcq_pack. */
 #define BCQ_LAYOUT_VERSION 2
+
+/* Most output rows (after padding to a multiple of 32) bcq_gemv_noalloc accepts. */
+#define BCQ_NOALLOC_MAX_ROWS 131072
 
 /* Largest batch bcq_gemm_skinny accepts. */
 #define BCQ_MAX_BATCH 64
@@ -211,6 +215,22 @@ bcq_status bcq_unpack(const bcq_desc *desc, const void *packed, uint8_t *codes,
  */
 bcq_status bcq_gemv(const bcq_desc *desc, const void *packed, const uint16_t *x,
                     uint16_t *y, void *workspace, void *stream);
+
+/*
+ * bcq_gemv without a workspace argument, for callers that cannot allocate device memory or size
+ * buffers at run time (code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc).  Same kernels and same result, bit for bit, as bcq_gemv; the split-K accumulators
+ * live in a static device array inside the library (8 bytes x BCQ_NOALLOC_MAX_ROWS = 1 MiB on
+ * every GPU the library is used on, held until the process ends).  The call allocates nothing and
+ * frees nothing: it looks up the array's device address (asked from the HIP runtime on the first
+ * call on each device, with that device current), clears the part it needs with a fill kernel and
+ * launches the GEMV, all on `stream`.  Rows beyond BCQ_NOALLOC_MAX_ROWS (M rounded up to 32) are
+ * refused with BCQ_ERR_SCRATCH_LIMIT before anything is launched.  All calls on one GPU share the
+ * one array: calls that overlap in time on the same GPU (different streams, or graph branches)
+ * race; serialise them.  packed, x, y as for bcq_gemv.
+ */
+bcq_status bcq_gemv_noalloc(const bcq_desc *desc, const void *packed, const uint16_t *x,
+                            uint16_t *y, void *stream);
 
 /*
  * Y[j][m] = sum_k W_q[m][k] X[j][k],  1 <= batch <= BCQ_MAX_BATCH (64).  The weights are read once

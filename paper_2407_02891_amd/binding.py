@@ -8,13 +8,14 @@ import os
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libbcq.so")
 
-BCQ_OK, BCQ_ERR_INVALID_ARG, BCQ_ERR_UNSUPPORTED, BCQ_ERR_WORKSPACE, BCQ_ERR_HIP = range(5)
+BCQ_OK, BCQ_ERR_INVALID_ARG, BCQ_ERR_UNSUPPORTED, BCQ_ERR_WORKSPACE, BCQ_ERR_HIP, BCQ_ERR_SCRATCH_LIMIT = range(6)
+BCQ_NOALLOC_MAX_ROWS = 131072
 BCQ_LAYOUT_VERSION = 2
 BCQ_MAX_BATCH = 64
 
 EXPORTS = ["bcq_packed_bytes", "bcq_workspace_bytes", "bcq_workspace_init", "bcq_pack",
            "bcq_pack_rows", "bcq_from_linear", "bcq_quant_workspace_bytes", "bcq_quant_hessian", "bcq_quant_factor_workspace_bytes", "bcq_quant_factor", "bcq_quant_search",
-           "bcq_quant_gptq", "bcq_from_linear_rows", "bcq_unpack", "bcq_gemv", "bcq_gemm_skinny", "bcq_read_probe_sink_bytes",
+           "bcq_quant_gptq", "bcq_from_linear_rows", "bcq_unpack", "bcq_gemv", "bcq_gemv_noalloc", "bcq_gemm_skinny", "bcq_read_probe_sink_bytes",
            "bcq_read_probe", "bcq_set_option", "bcq_status_string"]
 
 
@@ -64,6 +65,7 @@ def lib():
         L.bcq_from_linear_rows.argtypes = [i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]
         L.bcq_unpack.restype, L.bcq_unpack.argtypes = i32, [dp, vp, vp, vp, vp, vp]
         L.bcq_gemv.restype, L.bcq_gemv.argtypes = i32, [dp, vp, vp, vp, vp, vp]
+        L.bcq_gemv_noalloc.restype, L.bcq_gemv_noalloc.argtypes = i32, [dp, vp, vp, vp, vp]
         L.bcq_gemm_skinny.restype = i32
         L.bcq_gemm_skinny.argtypes = [dp, vp, vp, i32, vp, i32, i32, vp, vp]
         L.bcq_read_probe_sink_bytes.restype, L.bcq_read_probe_sink_bytes.argtypes = sz, []
@@ -175,6 +177,11 @@ def unpack(desc, packed, codes, alpha, offset, stream=None):
 def gemv(desc, packed, x, y, workspace, stream=None):
     _check(lib().bcq_gemv(ctypes.byref(desc), _ptr(packed), _ptr(x), _ptr(y), _ptr(workspace),
                           _stream(stream)), "bcq_gemv")
+
+
+def gemv_noalloc(desc, packed, x, y, stream=None):
+    _check(lib().bcq_gemv_noalloc(ctypes.byref(desc), _ptr(packed), _ptr(x), _ptr(y), _stream(stream)),
+           "bcq_gemv_noalloc")
 
 
 def gemm_skinny(desc, packed, X, ldx, Y, ldy, batch, workspace, stream=None):

@@ -235,6 +235,27 @@ bcq_status bcq_gemv(const bcq_desc *desc, const void *packed, const uint16_t *x,
     return bcq_gemm_skinny(desc, packed, x, desc->N, y, desc->M, 1, workspace, stream);
 }
 
+bcq_status bcq_gemv_noalloc(const bcq_desc *desc, const void *packed, const uint16_t *x, uint16_t *y, void *stream)
+{
+    bcq_status why;
+    if (!desc_ok(desc, &why)) return why;
+    if (desc->layout_version != BCQ_LAYOUT_VERSION) return BCQ_ERR_INVALID_ARG;
+    if (!packed || !x || !y) return BCQ_ERR_INVALID_ARG;
+    if (!aligned(packed, 256) || !aligned(x, 16) || !aligned(y, 2)) return BCQ_ERR_INVALID_ARG;
+    const Geom g = geom_of(desc);
+    if (g.Mp > kStaticScratchRows) return BCQ_ERR_SCRATCH_LIMIT;  // more rows than the static array holds
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    void *ws = nullptr;
+    const size_t need = workspace_bytes(g, 1);
+    if (need > 0) {
+        if (static_scratch(&ws) != hipSuccess) return BCQ_ERR_HIP;
+        // the array keeps whatever the last call on this GPU left (zeros, unless that call was cut short):
+        // clear the part this call uses, with a kernel rather than a memset node (the caller may be capturing)
+        if (launch_fill_zero(ws, need, s) != hipSuccess) return BCQ_ERR_HIP;
+    }
+    return launch_gemv(g, packed, x, y, ws, g_tuning, s) == hipSuccess ? BCQ_OK : BCQ_ERR_HIP;
+}
+
 size_t bcq_read_probe_sink_bytes(void) { return (size_t)kProbeBlocks * 4; }
 
 bcq_status bcq_read_probe(const void *buf, size_t bytes, void *sink, void *stream)
@@ -279,6 +300,7 @@ const char *bcq_status_string(bcq_status status)
         case BCQ_ERR_UNSUPPORTED: return "unsupported configuration";
         case BCQ_ERR_WORKSPACE: return "workspace missing or misaligned";
         case BCQ_ERR_HIP: return "HIP runtime error";
+        case BCQ_ERR_SCRATCH_LIMIT: return "more rows than the library's static scratch buffer holds";
     }
     return "unknown status";
 }

@@ -50,6 +50,11 @@ hipError_t launch_skinny(const Geom &g, const void *packed, const uint16_t *X, i
                          int batch, void *workspace, const GemvTuning &tuning, hipStream_t stream);
 hipError_t launch_read_probe(const void *buf, size_t bytes, void *sink, hipStream_t stream);
 
+// Rows the file-scope split-K scratch array covers (bcq_gemv_noalloc): 1 MiB per GPU.
+constexpr int kStaticScratchRows = 131072;
+// Device address of the current device's copy of that array (asked from the runtime on first use).
+hipError_t static_scratch(void **ptr);
+
 constexpr int kProbeBlocks = 512;  // the GEMV's grid: two workgroups per CU
 
 // Grid size the GEMV uses when none is forced.
