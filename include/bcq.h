@@ -212,6 +212,12 @@ bcq_status bcq_unpack(const bcq_desc *desc, const void *packed, uint8_t *codes,
  *   workspace DEVICE, bcq_workspace_bytes(desc, 1) bytes, 16-byte aligned,
  *             initialised once with bcq_workspace_init; may be NULL only if
  *             that size is 0
+ * Resolution of the split over columns (N > 512): every 512-column slice hands its fp32 partial sum of
+ * a row over as a multiple of 2^-34 (5.8e-11), so a result carries an absolute error of at most
+ * ceil(N/512) * 2^-35 on top of the fp32 rounding, whatever its size.  Against the 2e-3 relative
+ * tolerance (measured on max(|y|, rms(y)/64)) that is negligible as long as rms(y) >= 1e-6 *
+ * ceil(N/512); layers whose outputs are all smaller than that should be rescaled by the caller (alpha is
+ * linear in y).  Inputs must be finite: a non-finite activation gives unspecified output values.
  */
 bcq_status bcq_gemv(const bcq_desc *desc, const void *packed, const uint16_t *x,
                     uint16_t *y, void *workspace, void *stream);
@@ -233,7 +239,9 @@ bcq_status bcq_gemv_noalloc(const bcq_desc *desc, const void *packed, const uint
                             uint16_t *y, void *stream);
 
 /*
- * Y[j][m] = sum_k W_q[m][k] X[j][k],  1 <= batch <= BCQ_MAX_BATCH (64).  The weights are read once
+ * Y[j][m] = sum_k W_q[m][k] X[j][k],  1 <= batch <= BCQ_MAX_BATCH (64): the fused form of Eq. 11 applied
+ * to `batch` activation vectors at once (the paper measures batch 1 only, Sec. III "Speed up of GPTQT", and
+ * names larger batches as the method's limitation, Sec. IV).  The weights are read once
  * per call with groups that are multiples of 128 (or N), and once per 16 batch columns with
  * groups of 32/64.
  *   X   DEVICE, row j starts at X + j*ldx (elements), ldx >= N, ldx % 8 == 0

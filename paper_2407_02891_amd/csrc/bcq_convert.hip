@@ -11,32 +11,15 @@
 //   Eq. 11  W_hat = sum_c (S alpha_hat_c) b_c + ((2^n - 1)/2 S + qbias)
 #include "bcq_internal.h"
 #include "bcq_device.h"
+#include "bcq_tying.h"
 
 namespace bcq {
 
 struct ConvertPlan {
     int n_bits, q;
-    int nchoice;           // 2^q
-    int choice[16];        // members of BCchoice, ascending
-    int sign_bit[kMaxQ];   // output plane o takes its sign from this bit of the rounded integer
-    double alpha_hat[kMaxQ];  // sum of 2^(i-2) over the planes tied into output plane o, descending
-    double centre;         // (2^n - 1) / 2
+    TyingPlan tying;
+    double centre;  // (2^n - 1) / 2
 };
-
-// binary64 -> binary16, round to nearest even, with a single rounding: the value is first
-// rounded to binary32 *to odd* (truncate, then set the last bit if anything was lost), which
-// keeps enough information for the final rounding to be the correct one.
-__device__ __forceinline__ uint16_t double_to_half_bits(double v)
-{
-    float f = __double2float_rz(v);
-    if (static_cast<double>(f) != v && !(v != v)) {
-        uint32_t u = __builtin_bit_cast(uint32_t, f);
-        // |f| <= |v|: bump the magnitude's last bit when the truncation lost something (sticky bit)
-        u |= 1u;
-        f = __builtin_bit_cast(float, u);
-    }
-    return float_to_half_bits(f);
-}
 
 __global__ void from_linear_codes_kernel(ConvertPlan plan, const uint8_t *__restrict__ w_int,
                                          uint8_t *__restrict__ codes, size_t total)
@@ -44,16 +27,7 @@ __global__ void from_linear_codes_kernel(ConvertPlan plan, const uint8_t *__rest
     size_t gid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (gid >= total) return;
     const int w = w_int[gid] & ((1 << plan.n_bits) - 1);
-    // Eq. 6: nearest member of BCchoice; scanning upwards with a strict comparison keeps the
-    // smaller member on a tie
-    int best = plan.choice[0], best_d = abs(w - plan.choice[0]);
-    for (int k = 1; k < plan.nchoice; ++k) {
-        const int d = abs(w - plan.choice[k]);
-        if (d < best_d) { best_d = d; best = plan.choice[k]; }
-    }
-    uint8_t code = 0;
-    for (int o = 0; o < plan.q; ++o) code |= (uint8_t)(((best >> plan.sign_bit[o]) & 1) << o);
-    codes[gid] = code;
+    codes[gid] = code_of(nearest_choice(w, plan.tying.choice, plan.tying.nchoice), plan.tying, plan.q);  // Eq. 6
 }
 
 __global__ void from_linear_scales_kernel(ConvertPlan plan, const float *__restrict__ S,
@@ -63,7 +37,7 @@ __global__ void from_linear_scales_kernel(ConvertPlan plan, const float *__restr
     size_t gid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (gid >= total) return;
     const double s = static_cast<double>(S[gid]);
-    for (int o = 0; o < plan.q; ++o) alpha[gid * plan.q + o] = double_to_half_bits(s * plan.alpha_hat[o]);
+    for (int o = 0; o < plan.q; ++o) alpha[gid * plan.q + o] = double_to_half_bits(s * plan.tying.alpha_hat[o]);
     // the product is exact in binary64 (24-bit x 9-bit significands), the sum rounds once
     offset[gid] = double_to_half_bits(plan.centre * s + static_cast<double>(qbias[gid]));
 }
@@ -72,40 +46,11 @@ __global__ void from_linear_scales_kernel(ConvertPlan plan, const float *__restr
 // bit each output plane reads its sign from.  Returns false if a class is empty or a label is bad.
 bool make_convert_plan(int n_bits, int q, const int32_t *class_of_plane, ConvertPlan *plan)
 {
-    if (n_bits < 1 || n_bits > 8 || q < 1 || q > kMaxQ || q > n_bits || !class_of_plane) return false;
-    double ah[kMaxQ] = {0, 0, 0, 0};
-    int first_bit[kMaxQ] = {-1, -1, -1, -1};
-    for (int i = 0; i < n_bits; ++i) {  // plane i+1 of Eq. 9 is bit i, weight 2^(i-1)
-        const int c = class_of_plane[i];
-        if (c < 0 || c >= q) return false;
-        ah[c] += (double)(1 << i) / 2.0;
-        if (first_bit[c] < 0) first_bit[c] = i;
-    }
-    for (int c = 0; c < q; ++c)
-        if (first_bit[c] < 0) return false;
-    int order[kMaxQ] = {0, 1, 2, 3};
-    for (int a = 0; a < q; ++a)  // selection sort, descending; the sums are pairwise different
-        for (int b = a + 1; b < q; ++b)
-            if (ah[order[b]] > ah[order[a]]) { int t = order[a]; order[a] = order[b]; order[b] = t; }
-    plan->n_bits = n_bits; plan->q = q; plan->nchoice = 1 << q;
+    if (n_bits < 1 || n_bits > kMaxBits || q < 1 || q > kMaxQ || q > n_bits || !class_of_plane) return false;
+    plan->n_bits = n_bits;
+    plan->q = q;
     plan->centre = ((1 << n_bits) - 1) / 2.0;
-    for (int o = 0; o < q; ++o) {
-        plan->alpha_hat[o] = ah[order[o]];
-        plan->sign_bit[o] = first_bit[order[o]];
-    }
-    for (int m = 0; m < plan->nchoice; ++m) {  // every sign pattern of the q tied planes
-        int v = 0;
-        for (int i = 0; i < n_bits; ++i) {
-            int o = 0;
-            while (order[o] != class_of_plane[i]) ++o;
-            if ((m >> o) & 1) v |= 1 << i;
-        }
-        plan->choice[m] = v;
-    }
-    for (int a = 0; a < plan->nchoice; ++a)  // ascending
-        for (int b = a + 1; b < plan->nchoice; ++b)
-            if (plan->choice[b] < plan->choice[a]) { int t = plan->choice[a]; plan->choice[a] = plan->choice[b]; plan->choice[b] = t; }
-    return true;
+    return make_tying_plan(n_bits, q, class_of_plane, false, &plan->tying);
 }
 
 hipError_t launch_from_linear(int M, int N, int group, int n_bits, int q, const int32_t *class_of_plane,

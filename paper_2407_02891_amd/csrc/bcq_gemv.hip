@@ -41,6 +41,8 @@
 //  * When a 128-column block holds several scaling groups (group 32 or 64) the
 //    blob keeps each group in a fixed byte range of the lane's 16 bytes
 //    (bcq_layout.h), so a lane sums its lookups per range and applies one alpha each.
+#include <atomic>
+
 #include "bcq_internal.h"
 #include "bcq_device.h"
 
@@ -266,14 +268,35 @@ __global__ __launch_bounds__(NW * 64) void bcq_gemv_kernel(GemvParams p)
 // ---------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------
-constexpr int kResidentGroups = 2 * 256;  // 64 KB LDS each: two workgroups per CU, 256 CUs
+// Workgroups of the GEMV the current device holds at once: every instantiation uses 64 KB of LDS and at most 128
+// registers, so the occupancy of one of them, asked from the runtime once per device, stands for all (two per
+// compute unit on gfx950: 512 on an MI355X).
+int resident_gemv_groups()
+{
+    constexpr int kMaxDevices = 64;
+    static std::atomic<int> cached[kMaxDevices];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return 2 * 256;
+    int groups = cached[dev].load(std::memory_order_relaxed);
+    if (groups == 0) {
+        int per_cu = 0, cus = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, bcq_gemv_kernel<3, 0, 8, 1>, 8 * 64, 0) != hipSuccess ||
+            per_cu < 1)
+            per_cu = 2;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1) cus = 256;
+        groups = per_cu * cus;
+        cached[dev].store(groups, std::memory_order_relaxed);
+    }
+    return groups;
+}
 
 int auto_workgroups(const Geom &g, int waves_per_group)
 {
     // All workgroups resident at once and doing equal work; at least one tile per wave.
     long long tiles = (long long)g.nslice * g.ntile;
     long long groups = (tiles + waves_per_group - 1) / waves_per_group;
-    if (groups > kResidentGroups) groups = kResidentGroups;
+    const int resident = resident_gemv_groups();
+    if (groups > resident) groups = resident;
     if (groups < 1) groups = 1;
     return (int)groups;
 }
@@ -300,7 +323,7 @@ hipError_t launch_gemv(const Geom &g, const void *packed, const uint16_t *x, uin
     // 8 waves per workgroup (16 per CU) hide latency better once every wave still gets a tile;
     // the variants with several scaling groups per block exist with 4 waves only
     const long long tiles = (long long)g.nslice * g.ntile;
-    const int want = t.waves ? t.waves : (tiles >= 8LL * kResidentGroups ? 8 : 4);
+    const int want = t.waves ? t.waves : (tiles >= 8LL * resident_gemv_groups() ? 8 : 4);
     const int nw = (want == 8 && g.sub == 1) ? 8 : 4;
     int groups = t.workgroups > 0 ? t.workgroups : auto_workgroups(g, nw);
     // at least one workgroup per slice, at most one per row tile of a slice

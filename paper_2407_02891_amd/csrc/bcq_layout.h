@@ -1,4 +1,4 @@
-// Internal geometry of the packed weight blob (layout version 1), shared by the
+// Internal geometry of the packed weight blob (layout version 2), shared by the
 // pack, GEMV and skinny kernels of this library.  Not part of the public ABI.
 //
 // The weight of Eq. 11 (q sign planes, per-group alpha, optional offset) is cut

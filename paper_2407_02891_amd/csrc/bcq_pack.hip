@@ -133,6 +133,8 @@ hipError_t launch_pack(const Geom &g, int row0, int rows, const uint8_t *codes, 
     size_t ne = tiles * (size_t)g.scale_lanes * 2u * g.nsc;
     hipLaunchKernelGGL(pack_planes_kernel, dim3(blocks_for(nd, 256)), dim3(256), 0, stream, g, row0, rows,
                        codes, static_cast<uint8_t *>(packed), nd);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
     hipLaunchKernelGGL(pack_scales_kernel, dim3(blocks_for(ne, 256)), dim3(256), 0, stream, g, row0, rows,
                        alpha, offset, static_cast<uint8_t *>(packed), ne);
     return hipGetLastError();
@@ -146,6 +148,8 @@ hipError_t launch_unpack(const Geom &g, const void *packed, uint8_t *codes, uint
         size_t n = (size_t)g.M * g.N;
         hipLaunchKernelGGL(unpack_codes_kernel, dim3(blocks_for(n, 256)), dim3(256), 0, stream, g,
                            blob, codes);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
     }
     if (alpha || offset) {
         size_t n = (size_t)g.M * (g.N / g.group);

@@ -20,10 +20,9 @@
 
 #include "bcq_internal.h"
 #include "bcq_device.h"
+#include "bcq_tying.h"
 
 namespace bcq {
-
-constexpr int kMaxBits = 8;
 
 // One way of tying the planes: class of every bit, and the integers it can represent (ascending).
 struct Tying {
@@ -65,14 +64,10 @@ static std::vector<Tying> all_tyings(int n, int q)
         Tying t{};
         for (int c = 0; c < q; ++c)
             for (int plane : p[c]) t.label[plane - 1] = (int8_t)c;
-        t.nchoice = 1 << q;
-        for (int m = 0; m < t.nchoice; ++m) {
-            int v = 0;
-            for (int i = 0; i < n; ++i)
-                if ((m >> t.label[i]) & 1) v |= 1 << i;
-            t.choice[m] = v;
-        }
-        std::sort(t.choice, t.choice + t.nchoice);
+        TyingPlan plan;
+        make_tying_plan(n, q, t.label, false, &plan);
+        t.nchoice = plan.nchoice;
+        std::copy(plan.choice, plan.choice + plan.nchoice, t.choice);
         out.push_back(t);
     }
     return out;
@@ -84,13 +79,7 @@ __device__ __forceinline__ int quant_int(double w, double S, double qbias, int n
     double v = rint((w - qbias) / S);  // round half to even
     const double top = (double)((1 << n_bits) - 1);
     v = v < 0.0 ? 0.0 : (v > top ? top : v);
-    const int wi = (int)v;
-    int best = choice[0], best_d = abs(wi - choice[0]);
-    for (int k = 1; k < nchoice; ++k) {
-        const int d = abs(wi - choice[k]);
-        if (d < best_d) { best_d = d; best = choice[k]; }  // strict: the smaller member on a tie
-    }
-    return best;
+    return nearest_choice((int)v, choice, nchoice);
 }
 
 // ---------------------------------------------------------------------------------
@@ -625,31 +614,6 @@ hipError_t launch_quant_search(int M, int N, int n_bits, int q, int grid, const 
 // ---------------------------------------------------------------------------------
 // GPTQ pass
 // ---------------------------------------------------------------------------------
-// Labels come from device memory the host cannot inspect: out-of-range ones are folded into 0..q-1.
-__device__ __forceinline__ int class_of(const int8_t *label, int i, int q)
-{
-    const int c = label[i];
-    return c < 0 ? 0 : (c >= q ? q - 1 : c);
-}
-
-// BCchoice of a row from its class labels (ascending).
-__device__ __forceinline__ void row_choice(const int8_t *label, int n_bits, int q, int *choice)
-{
-    const int nc = 1 << q;
-    for (int m = 0; m < nc; ++m) {
-        int v = 0;
-        for (int i = 0; i < n_bits; ++i)
-            if ((m >> class_of(label, i, q)) & 1) v |= 1 << i;
-        choice[m] = v;
-    }
-    for (int a = 1; a < nc; ++a) {  // insertion sort
-        const int v = choice[a];
-        int b = a - 1;
-        while (b >= 0 && choice[b] > v) { choice[b + 1] = choice[b]; --b; }
-        choice[b + 1] = v;
-    }
-}
-
 // One block of up to 128 columns [c0, c1): one thread per row.  The block's columns of the row sit in
 // LDS; the 32 columns being decided are held in registers, where each decision's compensation reaches
 // the later ones of the 32 at once, and reach the block's remaining columns when the 32 are done
@@ -672,7 +636,9 @@ __global__ __launch_bounds__(kGptqRows) void gptq_block_kernel(int M, int Mp, in
     int choice[16];
     double s = 1.0, b = 0.0;
     if (live) {
-        row_choice(labels + (size_t)m * n_bits, n_bits, q, choice);
+        TyingPlan plan;  // labels come from device memory the host cannot inspect: out-of-range ones are folded
+        make_tying_plan(n_bits, q, labels + (size_t)m * n_bits, true, &plan);
+        for (int k = 0; k < 16; ++k) choice[k] = plan.choice[k];
         s = S[m]; b = qbias[m];
     }
     for (int j = 0; j < cols; ++j) wl[j][tm] = live ? Wt[(size_t)(c0 + j) * Mp + m] : 0.0f;
@@ -738,58 +704,23 @@ hipError_t launch_quant_gptq(int M, int N, int n_bits, int q, const float *W, co
 // ---------------------------------------------------------------------------------
 // fusion with one tying per row (row-wise parameters: one scaling group per row)
 // ---------------------------------------------------------------------------------
-__device__ __forceinline__ uint16_t double_to_half_bits_rne(double v)
-{
-    float f = __double2float_rz(v);
-    if (static_cast<double>(f) != v && !(v != v)) f = __builtin_bit_cast(float, __builtin_bit_cast(uint32_t, f) | 1u);
-    return float_to_half_bits(f);
-}
-
-// Per row: alpha_hat of every class, classes ordered by descending alpha_hat, the bit each output
-// plane reads its sign from.
-__device__ __forceinline__ void row_plan(const int8_t *label, int n_bits, int q, double *ah_sorted, int *sign_bit)
-{
-    double ah[kMaxQ] = {0, 0, 0, 0};
-    int first[kMaxQ] = {-1, -1, -1, -1};
-    for (int i = 0; i < n_bits; ++i) {
-        const int c = class_of(label, i, q);
-        ah[c] += (double)(1 << i) / 2.0;
-        if (first[c] < 0) first[c] = i;
-    }
-    int order[kMaxQ] = {0, 1, 2, 3};
-    for (int a = 0; a < q; ++a)
-        for (int b = a + 1; b < q; ++b)
-            if (ah[order[b]] > ah[order[a]]) { const int t = order[a]; order[a] = order[b]; order[b] = t; }
-    for (int o = 0; o < q; ++o) { ah_sorted[o] = ah[order[o]]; sign_bit[o] = first[order[o]] < 0 ? 0 : first[order[o]]; }
-}
-
 __global__ void from_linear_rows_kernel(int M, int N, int n_bits, int q, const int8_t *__restrict__ labels,
                                         const uint8_t *__restrict__ w_int, const float *__restrict__ S,
                                         const float *__restrict__ qbias, uint8_t *__restrict__ codes,
                                         uint16_t *__restrict__ alpha, uint16_t *__restrict__ offset)
 {
     const int m = blockIdx.x;
-    __shared__ int sign_bit[kMaxQ];
-    __shared__ int choice[16];
+    __shared__ TyingPlan plan;
     if (threadIdx.x == 0) {
-        double ah[kMaxQ];
-        row_plan(labels + (size_t)m * n_bits, n_bits, q, ah, sign_bit);
-        row_choice(labels + (size_t)m * n_bits, n_bits, q, choice);
+        make_tying_plan(n_bits, q, labels + (size_t)m * n_bits, true, &plan);
         const double s = S[m];
-        for (int o = 0; o < q; ++o) alpha[(size_t)m * q + o] = double_to_half_bits_rne(s * ah[o]);
-        offset[m] = double_to_half_bits_rne(((1 << n_bits) - 1) / 2.0 * s + (double)qbias[m]);
+        for (int o = 0; o < q; ++o) alpha[(size_t)m * q + o] = double_to_half_bits(s * plan.alpha_hat[o]);
+        offset[m] = double_to_half_bits(((1 << n_bits) - 1) / 2.0 * s + (double)qbias[m]);
     }
     __syncthreads();
     for (int k = threadIdx.x; k < N; k += blockDim.x) {
         const int w = w_int[(size_t)m * N + k] & ((1 << n_bits) - 1);
-        int best = choice[0], best_d = abs(w - choice[0]);  // Eq. 6 (members pass unchanged)
-        for (int c = 1; c < (1 << q); ++c) {
-            const int d = abs(w - choice[c]);
-            if (d < best_d) { best_d = d; best = choice[c]; }
-        }
-        uint8_t code = 0;
-        for (int o = 0; o < q; ++o) code |= (uint8_t)(((best >> sign_bit[o]) & 1) << o);
-        codes[(size_t)m * N + k] = code;
+        codes[(size_t)m * N + k] = code_of(nearest_choice(w, plan.choice, plan.nchoice), plan, q);  // Eq. 6 (members pass unchanged)
     }
 }
 

@@ -40,6 +40,8 @@
 //    ones: the block's column sums of X, scaled by z.  Bound: LDS read bandwidth.
 //  In both, the pairing inside an octet (elements 2d, 2d+1 <-> columns d, d+4) is arbitrary as
 //  long as A and B agree; X is stored in LDS in that order.
+#include <atomic>
+
 #include "bcq_internal.h"
 #include "bcq_device.h"
 
@@ -567,19 +569,23 @@ __global__ __launch_bounds__(64 * NW) void bcq_skinny_kernel(SkinnyParams p)
 template <int Q, int Z, int SUB, int VER, int LDS_STEPS, int NB, int NW>
 static int resident_groups()
 {
-    static int cached = 0;
-    if (cached == 0) {
-        int per_cu = 0, dev = 0, cus = 0;
+    constexpr int kMaxDevices = 64;
+    static std::atomic<int> cached[kMaxDevices];  // per device (zero-initialised)
+    int dev = 0;
+    const bool known = hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < kMaxDevices;
+    int groups = known ? cached[dev].load(std::memory_order_relaxed) : 0;
+    if (groups == 0) {
+        int per_cu = 0, cus = 0;
         if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, bcq_skinny_kernel<Q, Z, SUB, VER, LDS_STEPS, NB, NW>, 64 * NW,
                                                          0) != hipSuccess ||
             per_cu < 1)
             per_cu = 1;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+        if (!known || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
             cus = 256;
-        cached = per_cu * cus;
+        groups = per_cu * cus;
+        if (known) cached[dev].store(groups, std::memory_order_relaxed);
     }
-    return cached;
+    return groups;
 }
 
 // Grid size: `parts` > 0: that many workgroups per tile group (a K split); `parts` < 0: -parts

@@ -165,6 +165,21 @@ def test_gemm_skinny_refuses_a_batch_beyond_the_workspace():
     assert e.value.status == bcq.binding.BCQ_ERR_INVALID_ARG
 
 
+@pytest.mark.parametrize("shift,ok", [(8, True), (12, True)])
+def test_small_outputs_and_the_split_k_quantum(shift, ok):
+    """Partial sums cross the column slices as multiples of 2^-34, so a result carries an absolute error of up
+    to ceil(N/512) * 2^-35 whatever its size.  With every alpha scaled down by 2^shift (rms(y) ~ 6e-3 and
+    4e-4 here, 16 slices) the gate still holds with room: the documented floor is rms(y) >= 1e-6 * ceil(N/512)."""
+    L = bcq_synth.make_layer(128, 8192, 3, group=128, offset=False, batch=4, seed=17)
+    L.alpha = (L.alpha.astype(np.float32) * 2.0 ** -shift).astype(np.float16)
+    y_ref = ref.gemm(L.planes, L.alpha, None, L.x)
+    rms = float(np.sqrt(np.mean(y_ref ** 2)))
+    assert rms >= 1e-6 * 16 * 8, rms
+    pl = U.upload_and_pack(L, max_batch=4)
+    U.gate(U.gpu_gemv(pl, U.x_dev(L))[None, :], y_ref[:1], f"small outputs, rms {rms:.1e}")
+    U.gate(U.gpu_gemm(pl, U.x_dev(L)), y_ref, f"small outputs skinny, rms {rms:.1e}")
+
+
 @pytest.mark.parametrize("batch", [2, 4, 8, 16])
 def test_skinny_batches(batch):
     _run_case(160, 1536, 3, 128, True, batch=batch, seed=batch)
