@@ -93,11 +93,48 @@ __device__ __forceinline__ unsigned long long encode_partial(float v)
     return (static_cast<unsigned long long>(fixed) << kCountBits) + 1ull;
 }
 
+// The same word without binary64 instructions (about half the vector-ALU work; used by the GEMV, whose
+// loop is short enough for it to matter).
+__device__ __forceinline__ unsigned long long encode_partial_f32(float v)
+{
+    // keep the conversion in range; magnitudes this large cannot end in a finite binary16
+    v = fminf(fmaxf(v, -536870848.0f), 536870848.0f);  // |v| < 2^29
+    // round(v * 2^34) as a 64-bit two's complement integer, in binary32 steps that are all exact: the
+    // product is a power-of-two scaling; rintf leaves an integer m of at most 24 significant bits below
+    // 2^63; its magnitude splits as hi * 2^32 + lo with 0 <= lo < 2^32, both representable (when hi > 0,
+    // lo is a multiple of ulp(m) >= 2^9).  The sign is applied to the 64-bit integer afterwards (a
+    // negative value cannot be split the same way: -5 = -1 * 2^32 + 4294967291 needs 32 bits).
+    const float m = fabsf(rintf(v * 17179869184.0f));
+    const float hi = floorf(m * 2.3283064365386963e-10f);
+    const float lo = fmaf(-hi, 4294967296.0f, m);
+    const unsigned long long mag = (static_cast<unsigned long long>(static_cast<unsigned>(hi)) << 32) |
+                                   static_cast<unsigned long long>(static_cast<unsigned>(lo));
+    // two's complement negation where v is negative, without a lane mask: (mag ^ s) - s, s = 0 or all ones
+    const unsigned long long sgn = static_cast<unsigned long long>(static_cast<long long>(static_cast<int>(__float_as_uint(v)) >> 31));
+    const unsigned long long fixed = (mag ^ sgn) - sgn;
+    return (fixed << kCountBits) + 1ull;
+}
+
 // Value of a completed accumulator word (arrival count dropped).
 __device__ __forceinline__ float decode_total(unsigned long long total)
 {
     const long long fixed = static_cast<long long>(total) >> kCountBits;
     return static_cast<float>(static_cast<double>(fixed) * (1.0 / kFixedScale));
+}
+
+// Sum over the four lanes l, l^16, l^32, l^48 (the owners of the four 128-column blocks of a row) of `a0`
+// in the lanes 0..15 (and 16..31) and of `a1` in the lanes 32..47 (and 48..63), with two lane-swap
+// instructions on the vector ALU instead of four trips through the LDS crossbar.
+__device__ __forceinline__ float sum_block_owners(float a0, float a1)
+{
+    // upper half of a0 <-> lower half of a1: lanes 0..31 then hold a0's two row pairs, lanes 32..63 a1's
+    const auto h = __builtin_amdgcn_permlane32_swap(__float_as_uint(a0), __float_as_uint(a1), false, false);
+    const unsigned h0 = h[0], h1 = h[1];  // (element reads first: a bit cast straight from h[1] reads h[0])
+    const float s = __uint_as_float(h0) + __uint_as_float(h1);
+    // odd 16-lane rows of one copy <-> even rows of the other: every row of 16 lanes then sees both halves
+    const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(s), __float_as_uint(s), false, false);
+    const unsigned r0 = r[0], r1 = r[1];
+    return __uint_as_float(r0) + __uint_as_float(r1);
 }
 
 __device__ __forceinline__ unsigned arrivals_of(unsigned long long total)

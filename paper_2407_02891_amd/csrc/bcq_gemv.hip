@@ -21,7 +21,8 @@
 //  * The LDS byte address (index*256 + 4*chunk) is assembled by one v_perm_b32
 //    from a byte of the plane word and a byte of a per-lane constant.
 //  * Lanes accumulate privately in fp32; the four block owners of a row are
-//    summed with two cross-lane steps once per 32-row tile.
+//    summed once per 32-row tile with two lane-swap instructions
+//    (v_permlane32_swap, v_permlane16_swap: vector ALU, no trip through LDS).
 //  * Column slices are combined with ONE device-scope 64-bit integer atomic per
 //    row and slice: the fp32 partial is converted to fixed point (2^-34 units,
 //    54 bits, two's complement, wrapping) and added, together with an arrival
@@ -125,12 +126,13 @@ __global__ __launch_bounds__(NW * 64) void bcq_gemv_kernel(GemvParams p)
             part = rest - (rest / parts) * parts;
         }
     }
-    const int waves_per_slice = parts * NW;
-
-    // Row tiles of this wave: an even split of the ntile tiles over all waves of the slice.
-    const int gw = part * NW + wave;
-    const int t_begin = (int)(((long long)gw * p.ntile) / waves_per_slice);
-    const int t_end = (int)(((long long)(gw + 1) * p.ntile) / waves_per_slice);
+    // Row tiles of this workgroup: an even split of the slice's tiles over its workgroups.  Inside the
+    // workgroup wave w takes the tiles first + w, first + w + NW, ...: at any moment the workgroup
+    // streams NW neighbouring tiles (one contiguous stretch of the blob), which the memory system serves
+    // better than NW separate streams.
+    const int g_begin = (int)(((long long)part * p.ntile) / parts);
+    const int t_end = (int)(((long long)(part + 1) * p.ntile) / parts);
+    const int t_begin = g_begin + wave < t_end ? g_begin + wave : t_end;
     const uint8_t *tile_ptr = p.blob + ((size_t)slice * p.ntile + t_begin) * p.tile_bytes;
 
     // Start the first tile's loads before building the tables.
@@ -201,25 +203,27 @@ __global__ __launch_bounds__(NW * 64) void bcq_gemv_kernel(GemvParams p)
     //   (c) issues the atomic of tile k-1, whose partial was kept in a register;
     //   (d) starts the loads of tile k+1;  (e) computes tile k.
     const bool split_k = p.nslice > 1;
+    const bool reporter = (lane & 16) == 0;                      // lanes 0..15 and 32..47
+    const int rep_row = (lane & 15) | ((lane >> 5) << 4);        // their row inside the tile
     int held_tile = -1;  // computed, partial still in `held`
     float held = 0.0f;
     int pend_tile = -1;  // atomic issued, result pending
     unsigned long long pend_old = 0, pend_mine = 0;
 
-    for (int tile = t_begin; tile < t_end; ++tile) {
+    for (int tile = t_begin; tile < t_end; tile += NW) {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // (a)
-        if (split_k && lane < 32) {
-            if (pend_tile >= 0) complete_row(p, pend_tile * kTileRows + lane, pend_old + pend_mine);  // (b)
+        if (split_k && reporter) {
+            if (pend_tile >= 0) complete_row(p, pend_tile * kTileRows + rep_row, pend_old + pend_mine);  // (b)
             pend_tile = held_tile;
             if (held_tile >= 0) {  // (c)
-                pend_mine = encode_partial(held);
-                pend_old = __hip_atomic_fetch_add(p.accum + held_tile * kTileRows + lane, pend_mine,
+                pend_mine = encode_partial_f32(held);
+                pend_old = __hip_atomic_fetch_add(p.accum + held_tile * kTileRows + rep_row, pend_mine,
                                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
         TileRegs<Q, Z, SUB> nxt;
-        tile_ptr += p.tile_bytes;
-        if (tile + 1 < t_end) load_tile<Q, Z, SUB>(nxt, tile_ptr, lane, lane & p.scale_lane_mask);  // (d)
+        tile_ptr += (size_t)NW * p.tile_bytes;
+        if (tile + NW < t_end) load_tile<Q, Z, SUB>(nxt, tile_ptr, lane, lane & p.scale_lane_mask);  // (d)
 
         float acc[2];  // (e)
 #pragma unroll
@@ -236,31 +240,30 @@ __global__ __launch_bounds__(NW * 64) void bcq_gemv_kernel(GemvParams p)
 #pragma unroll
                 for (int g = 0; g < SUB; ++g) a = fmaf(scale_of<Q, Z, SUB>(cur, t, g, Q), xsum[g], a);
             }
-            // sum the four block owners (lanes r, r+16, r+32, r+48) of each row
-            a += __shfl_xor(a, 16, 64);
-            a += __shfl_xor(a, 32, 64);
             acc[t] = a;
         }
-        const float out = (lane & 16) ? acc[1] : acc[0];  // lanes 0..31 <-> rows 0..31 of the tile
+        // the four block owners (lanes r, r+16, r+32, r+48) of each row summed: rows 0..15 of the tile
+        // end up in the lanes 0..15, rows 16..31 in the lanes 32..47 (the reporters)
+        const float out = sum_block_owners(acc[0], acc[1]);
         if (split_k) {
             held = out;
             held_tile = tile;
         } else {
-            const int row = tile * kTileRows + (lane & 31);
-            if (lane < 32 && row < p.M) p.y[row] = float_to_half_bits(out);
+            const int row = tile * kTileRows + rep_row;
+            if (reporter && row < p.M) p.y[row] = float_to_half_bits(out);
         }
-        if (tile + 1 < t_end) cur = nxt;
+        if (tile + NW < t_end) cur = nxt;
     }
 
-    if (split_k && lane < 32) {  // drain: two tiles may still be in the pipeline
+    if (split_k && reporter) {  // drain: two tiles may still be in the pipeline
         if (held_tile >= 0) {
-            const unsigned long long mine = encode_partial(held);
-            const unsigned long long old = __hip_atomic_fetch_add(p.accum + held_tile * kTileRows + lane, mine,
+            const unsigned long long mine = encode_partial_f32(held);
+            const unsigned long long old = __hip_atomic_fetch_add(p.accum + held_tile * kTileRows + rep_row, mine,
                                                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (pend_tile >= 0) complete_row(p, pend_tile * kTileRows + lane, pend_old + pend_mine);
-            complete_row(p, held_tile * kTileRows + lane, old + mine);
+            if (pend_tile >= 0) complete_row(p, pend_tile * kTileRows + rep_row, pend_old + pend_mine);
+            complete_row(p, held_tile * kTileRows + rep_row, old + mine);
         } else if (pend_tile >= 0) {
-            complete_row(p, pend_tile * kTileRows + lane, pend_old + pend_mine);
+            complete_row(p, pend_tile * kTileRows + rep_row, pend_old + pend_mine);
         }
     }
 }
