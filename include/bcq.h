@@ -267,7 +267,9 @@ bcq_status bcq_read_probe(const void *buf, size_t bytes, void *sink, void *strea
  * Launch-shape overrides for tuning runs (HOST state, process-wide, not
  * thread-safe).  Names: "workgroups" (grid size of the GEMV and of the skinny
  * kernel), "waves" (waves per workgroup, 4 or 8: the GEMV, the table kernel of
- * bcq_gemm_skinny up to 16 columns and its 32-column pass), "skinny_parts" (K
+ * bcq_gemm_skinny up to 16 columns and its 32-column pass), "gemv_early" (1 = the GEMV
+ * builds its tables before its first tile has arrived, 2 = never; automatic: when no wave has
+ * more than one tile), "skinny_parts" (K
  * split of bcq_gemm_skinny for batch >= 2), "skinny_version" (1 = the kernel
  * that folds alpha into the matrix-core operand, 2 = the kernel that takes +-1
  * operands from an LDS table, with q = 4 at most 32 columns per pass; groups of

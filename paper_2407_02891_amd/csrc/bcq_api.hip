@@ -277,6 +277,10 @@ bcq_status bcq_set_option(const char *name, int32_t value)
         g_tuning.waves = value;
         return BCQ_OK;
     }
+    if (strcmp(name, "gemv_early") == 0 && value <= 2) {
+        g_tuning.early = value;
+        return BCQ_OK;
+    }
     if (strcmp(name, "skinny_parts") == 0) {
         g_tuning.skinny_parts = value;
         return BCQ_OK;

@@ -105,7 +105,11 @@ __device__ __forceinline__ void complete_row(const GemvParams &p, int row, unsig
     }
 }
 
-template <int Q, int Z, int NW, int SUB>
+// EARLY = 1: no branch around the first loads (addresses are clamped instead), so that the wait in front of
+// the table build can be for the activations alone and the tables are built while the first tile is still
+// on its way.  Pays when a wave has a single tile (small layers: the kernel is one latency chain); with
+// several tiles per wave it measured slower than waiting for both, so the launcher picks.
+template <int Q, int Z, int NW, int SUB, int EARLY = 0>
 __global__ __launch_bounds__(NW * 64) void bcq_gemv_kernel(GemvParams p)
 {
     __shared__ float lut[256 * 64];  // 64 KB: entry idx of chunk c at lut[idx*64 + c]
@@ -139,8 +143,17 @@ __global__ __launch_bounds__(NW * 64) void bcq_gemv_kernel(GemvParams p)
     TileRegs<Q, Z, SUB> cur;
     const int col0 = slice * kTileCols + kChunkCols * lane;  // lane = chunk
     u32x4 xr = {0u, 0u, 0u, 0u};
-    if (col0 < p.N) xr = *reinterpret_cast<const u32x4 *>(p.x + col0);
-    if (t_begin < t_end) load_tile<Q, Z, SUB>(cur, tile_ptr, lane, lane & p.scale_lane_mask);
+    if (EARLY) {
+        xr = *reinterpret_cast<const u32x4 *>(p.x + (col0 < p.N ? col0 : 0));
+        // a wave without tiles reads the slice's last tile and drops it
+        const int t_first = t_begin < p.ntile ? t_begin : p.ntile - 1;
+        load_tile<Q, Z, SUB>(cur, p.blob + ((size_t)slice * p.ntile + t_first) * p.tile_bytes, lane,
+                             lane & p.scale_lane_mask);
+        if (col0 >= p.N) xr = u32x4{0u, 0u, 0u, 0u};
+    } else {
+        if (col0 < p.N) xr = *reinterpret_cast<const u32x4 *>(p.x + col0);
+        if (t_begin < t_end) load_tile<Q, Z, SUB>(cur, tile_ptr, lane, lane & p.scale_lane_mask);
+    }
 
     // ---- sign-sum tables for the 512 activations of this slice ----------------
     {
@@ -304,19 +317,20 @@ int auto_workgroups(const Geom &g, int waves_per_group)
     return (int)groups;
 }
 
-template <int Q, int Z, int NW, int SUB>
+template <int Q, int Z, int NW, int SUB, int EARLY = 0>
 static hipError_t launch_one(const GemvParams &p, int groups, hipStream_t stream)
 {
-    hipLaunchKernelGGL((bcq_gemv_kernel<Q, Z, NW, SUB>), dim3((unsigned)groups), dim3(NW * 64), 0,
+    hipLaunchKernelGGL((bcq_gemv_kernel<Q, Z, NW, SUB, EARLY>), dim3((unsigned)groups), dim3(NW * 64), 0,
                        stream, p);
     return hipGetLastError();
 }
 
 template <int Q, int Z>
-static hipError_t launch_qz(const GemvParams &p, int waves, int sub, int groups, hipStream_t stream)
+static hipError_t launch_qz(const GemvParams &p, int waves, int sub, int groups, bool early, hipStream_t stream)
 {
     if (sub == 2) return launch_one<Q, Z, 4, 2>(p, groups, stream);
     if (sub == 4) return launch_one<Q, Z, 4, 4>(p, groups, stream);
+    if (early) return waves == 8 ? launch_one<Q, Z, 8, 1, 1>(p, groups, stream) : launch_one<Q, Z, 4, 1, 1>(p, groups, stream);
     return waves == 8 ? launch_one<Q, Z, 8, 1>(p, groups, stream) : launch_one<Q, Z, 4, 1>(p, groups, stream);
 }
 
@@ -326,7 +340,9 @@ hipError_t launch_gemv(const Geom &g, const void *packed, const uint16_t *x, uin
     // 8 waves per workgroup (16 per CU) hide latency better once every wave still gets a tile;
     // the variants with several scaling groups per block exist with 4 waves only
     const long long tiles = (long long)g.nslice * g.ntile;
-    const int want = t.waves ? t.waves : (tiles >= 8LL * resident_gemv_groups() ? 8 : 4);
+    // measured: from about four tiles per resident workgroup on, eight waves win (7168 x 7168: 392 workgroups of
+    // 8 waves with one tile each 7.4 us, 512 of 4 waves 8.0 us; 1024 x 8192: 4 waves 4.2 us, 8 waves 4.7 us)
+    const int want = t.waves ? t.waves : (tiles >= 4LL * resident_gemv_groups() ? 8 : 4);
     const int nw = (want == 8 && g.sub == 1) ? 8 : 4;
     int groups = t.workgroups > 0 ? t.workgroups : auto_workgroups(g, nw);
     // at least one workgroup per slice, at most one per row tile of a slice
@@ -343,16 +359,19 @@ hipError_t launch_gemv(const Geom &g, const void *packed, const uint16_t *x, uin
     p.ntile = g.ntile; p.nslice = g.nslice;
     p.tile_bytes = g.tile_bytes;
     p.scale_lane_mask = g.scale_lanes - 1;
+    // one tile per wave at most: the early table build pays (measured: 7168 x 7168 8.0 -> 7.4 us, 8192 x 8192
+    // 8.55 -> 8.3 us, 1024 x 8192 5.0 -> 4.2 us; with more tiles per wave it loses 1.5-2 us on the large layers)
+    const bool early = t.early ? t.early == 1 : tiles <= (long long)groups * nw;
     const int key = g.q * 2 + g.z;
     switch (key) {
-        case 2: return launch_qz<1, 0>(p, nw, g.sub, groups, stream);
-        case 3: return launch_qz<1, 1>(p, nw, g.sub, groups, stream);
-        case 4: return launch_qz<2, 0>(p, nw, g.sub, groups, stream);
-        case 5: return launch_qz<2, 1>(p, nw, g.sub, groups, stream);
-        case 6: return launch_qz<3, 0>(p, nw, g.sub, groups, stream);
-        case 7: return launch_qz<3, 1>(p, nw, g.sub, groups, stream);
-        case 8: return launch_qz<4, 0>(p, nw, g.sub, groups, stream);
-        case 9: return launch_qz<4, 1>(p, nw, g.sub, groups, stream);
+        case 2: return launch_qz<1, 0>(p, nw, g.sub, groups, early, stream);
+        case 3: return launch_qz<1, 1>(p, nw, g.sub, groups, early, stream);
+        case 4: return launch_qz<2, 0>(p, nw, g.sub, groups, early, stream);
+        case 5: return launch_qz<2, 1>(p, nw, g.sub, groups, early, stream);
+        case 6: return launch_qz<3, 0>(p, nw, g.sub, groups, early, stream);
+        case 7: return launch_qz<3, 1>(p, nw, g.sub, groups, early, stream);
+        case 8: return launch_qz<4, 0>(p, nw, g.sub, groups, early, stream);
+        case 9: return launch_qz<4, 1>(p, nw, g.sub, groups, early, stream);
     }
     return hipErrorInvalidValue;
 }

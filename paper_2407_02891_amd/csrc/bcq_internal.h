@@ -38,6 +38,7 @@ bool make_convert_plan(int n_bits, int q, const int32_t *class_of_plane, Convert
 struct GemvTuning {
     int workgroups = 0; // grid size
     int waves = 0;      // waves per workgroup: 4 or 8
+    int early = 0;      // GEMV: 1 = build the tables before the first tile has arrived, 2 = never, 0 = automatic
     int skinny_parts = 0;  // K split of the skinny kernel
     int skinny_version = 0;    // 1 = the first skinny kernel (alpha folded into A) also where the second applies
     int skinny_lds_steps = 0;  // second skinny kernel: MFMA steps per block whose A operand comes from the

@@ -104,6 +104,26 @@ def test_grid_size_does_not_change_results():
     U.gate(outs[0].view(np.float16)[None, :], ref.gemm(L.planes, L.alpha, L.offset, L.x))
 
 
+@pytest.mark.parametrize("early", [1, 2])
+@pytest.mark.parametrize("waves", [4, 8])
+def test_gemv_early_table_build_and_wave_count_do_not_change_results(early, waves):
+    """The GEMV in both start-up orders (tables built before / after the first tile has arrived) and with 4 and
+    8 waves per workgroup, forced on shapes that the automatic choice would run otherwise: bit for bit the
+    oracle's result on exact inputs (ragged rows and columns, waves without a tile), gate on random ones."""
+    try:
+        bcq.set_option("gemv_early", early)
+        bcq.set_option("waves", waves)
+        for (M, N, q, off) in [(70, 1536, 3, True), (1000, 2592 - 32, 2, False), (40, 512, 4, True)]:
+            group = 128 if N % 128 == 0 else N
+            L = bcq_synth.make_exact_layer(M, N, q, group=group, offset=off, seed=M + q + early)
+            y = U.gpu_gemv(U.upload_and_pack(L), U.x_dev(L)).astype(np.float64)
+            assert np.array_equal(y, ref.gemm(L.planes, L.alpha, L.offset, L.x)[0]), (M, N, q, off)
+        _run_case(600, 4096, 3, 128, True, seed=early + waves)
+    finally:
+        bcq.set_option("gemv_early", 0)
+        bcq.set_option("waves", 0)
+
+
 def test_subnormal_alpha_and_zero_inputs():
     L = bcq_synth.make_layer(64, 1024, 3, group=128, offset=False, seed=5)
     a = L.alpha.view(np.uint16).copy()
