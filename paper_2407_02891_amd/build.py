@@ -16,8 +16,23 @@ HIPCC_FLAGS = [
 ]
 
 
+TRACE_LIB = os.path.join(HERE, "libbcq_trace.so")
+
+
 def sources():
-    return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
+    """Sources of libbcq.so: every .hip file except the tracing build's entry points."""
+    return sorted(f for f in glob.glob(os.path.join(CSRC, "*.hip")) if not f.endswith("bcq_trace_api.hip"))
+
+
+def build_trace(verbose=False):
+    """libbcq_trace.so: the GEMV compiled with per-wave time stamps (-DBCQ_TRACE), for trace_gemv.py."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    srcs = [os.path.join(CSRC, f) for f in ("bcq_gemv.hip", "bcq_pack.hip", "bcq_trace_api.hip")]
+    cmd = [hipcc] + HIPCC_FLAGS + ["-DBCQ_TRACE"] + srcs + ["-o", TRACE_LIB]
+    if verbose:
+        print(" ".join(cmd))
+    subprocess.run(cmd, check=True, stderr=subprocess.DEVNULL if not verbose else None)
+    return TRACE_LIB
 
 
 def kernel_resources(stderr_text):
@@ -74,4 +89,5 @@ def build(verbose=False, extra_flags=()):
 
 
 if __name__ == "__main__":
-    print(build(verbose=True))
+    import sys
+    print(build_trace(verbose=True) if "--trace" in sys.argv else build(verbose=True))

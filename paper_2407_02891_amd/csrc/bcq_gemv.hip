@@ -59,7 +59,27 @@ struct GemvParams {
     int parts, big_slices;  // slices [0, big_slices) have parts+1 workgroups, the others parts
     unsigned tile_bytes;
     int scale_lane_mask;  // 63: one scale record per lane; 15: one per row (group = N)
+#ifdef BCQ_TRACE
+    unsigned *trace;      // [workgroup][wave][kTraceSlots] time stamps (the tracing build only)
+#endif
 };
+
+// Per-wave timeline for the tracing build (libbcq_trace.so, see trace_gemv.py): the 100 MHz real-time counter
+// at fixed points, and the time spent in each part of the tile loop summed over the wave's tiles.  The normal
+// build compiles none of this.
+#ifdef BCQ_TRACE
+#define BCQ_STAMP(i) (ts[i] = (unsigned)__builtin_amdgcn_s_memrealtime())
+#define BCQ_PHASE(i)                                                      \
+    do {                                                                  \
+        asm volatile("" ::: "memory");                                    \
+        const unsigned now_ = (unsigned)__builtin_amdgcn_s_memrealtime(); \
+        ts[i] += now_ - tphase;                                           \
+        tphase = now_;                                                    \
+    } while (0)
+#else
+#define BCQ_STAMP(i) ((void)0)
+#define BCQ_PHASE(i) ((void)0)
+#endif
 
 
 // One table lookup: byte `n` of plane word `w` is the index, byte `n` of `rv`
@@ -113,6 +133,10 @@ template <int Q, int Z, int NW, int SUB, int EARLY = 0>
 __global__ __launch_bounds__(NW * 64) void bcq_gemv_kernel(GemvParams p)
 {
     __shared__ float lut[256 * 64];  // 64 KB: entry idx of chunk c at lut[idx*64 + c]
+#ifdef BCQ_TRACE
+    unsigned ts[kTraceSlots] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0}, tphase = 0;
+#endif
+    BCQ_STAMP(0);  // wave started
 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
@@ -155,6 +179,7 @@ __global__ __launch_bounds__(NW * 64) void bcq_gemv_kernel(GemvParams p)
         if (t_begin < t_end) load_tile<Q, Z, SUB>(cur, tile_ptr, lane, lane & p.scale_lane_mask);
     }
 
+    BCQ_STAMP(1);  // first loads issued
     // ---- sign-sum tables for the 512 activations of this slice ----------------
     {
         float xv[8];
@@ -162,6 +187,10 @@ __global__ __launch_bounds__(NW * 64) void bcq_gemv_kernel(GemvParams p)
         xv[2] = half_bits_to_float(xr.y & 0xffffu); xv[3] = half_bits_to_float(xr.y >> 16);
         xv[4] = half_bits_to_float(xr.z & 0xffffu); xv[5] = half_bits_to_float(xr.z >> 16);
         xv[6] = half_bits_to_float(xr.w & 0xffffu); xv[7] = half_bits_to_float(xr.w >> 16);
+#ifdef BCQ_TRACE
+        asm volatile("" ::"v"(xv[0]), "v"(xv[7]));
+#endif
+        BCQ_STAMP(2);  // activations in registers (and, without EARLY, the first tile too)
 
         constexpr int IPW = 256 / NW;               // indices built by one wave
         constexpr int LB = (IPW == 64) ? 6 : (IPW == 32) ? 5 : (IPW == 128) ? 7 : 4;
@@ -183,7 +212,9 @@ __global__ __launch_bounds__(NW * 64) void bcq_gemv_kernel(GemvParams p)
             for (int a = 0; a < 8; ++a) lut[(wave * IPW + m * 8 + a) * 64 + lane] = lo[a] + mid;
         }
     }
+    BCQ_STAMP(3);  // this wave's share of the tables written
     __syncthreads();
+    BCQ_STAMP(4);  // tables complete
 
     // ---- per-lane constants ----------------------------------------------------
     const int r = lane & 15, h = lane >> 4;
@@ -224,7 +255,15 @@ __global__ __launch_bounds__(NW * 64) void bcq_gemv_kernel(GemvParams p)
     unsigned long long pend_old = 0, pend_mine = 0;
 
     for (int tile = t_begin; tile < t_end; tile += NW) {
+#ifdef BCQ_TRACE
+        tphase = (unsigned)__builtin_amdgcn_s_memrealtime();
+#endif
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // (a)
+#ifdef BCQ_TRACE
+        if (tile == t_begin) BCQ_STAMP(5);  // first tile in registers
+        ts[15] += 1;
+#endif
+        BCQ_PHASE(8);  // waiting for the tile (and the atomic two tiles back)
         if (split_k && reporter) {
             if (pend_tile >= 0) complete_row(p, pend_tile * kTileRows + rep_row, pend_old + pend_mine);  // (b)
             pend_tile = held_tile;
@@ -234,9 +273,11 @@ __global__ __launch_bounds__(NW * 64) void bcq_gemv_kernel(GemvParams p)
                                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
+        BCQ_PHASE(9);  // completing rows, issuing the atomic
         TileRegs<Q, Z, SUB> nxt;
         tile_ptr += (size_t)NW * p.tile_bytes;
         if (tile + NW < t_end) load_tile<Q, Z, SUB>(nxt, tile_ptr, lane, lane & p.scale_lane_mask);  // (d)
+        BCQ_PHASE(10);  // issuing the next tile's loads (stalls here when the memory pipeline is full)
 
         float acc[2];  // (e)
 #pragma unroll
@@ -257,6 +298,10 @@ __global__ __launch_bounds__(NW * 64) void bcq_gemv_kernel(GemvParams p)
         }
         // the four block owners (lanes r, r+16, r+32, r+48) of each row summed: rows 0..15 of the tile
         // end up in the lanes 0..15, rows 16..31 in the lanes 32..47 (the reporters)
+#ifdef BCQ_TRACE
+        asm volatile("" ::"v"(acc[0]), "v"(acc[1]));
+#endif
+        BCQ_PHASE(11);  // table look-ups and scaling
         const float out = sum_block_owners(acc[0], acc[1]);
         if (split_k) {
             held = out;
@@ -265,8 +310,13 @@ __global__ __launch_bounds__(NW * 64) void bcq_gemv_kernel(GemvParams p)
             const int row = tile * kTileRows + rep_row;
             if (reporter && row < p.M) p.y[row] = float_to_half_bits(out);
         }
+#ifdef BCQ_TRACE
+        asm volatile("" ::"v"(out));
+#endif
+        BCQ_PHASE(12);  // cross-lane sum
         if (tile + NW < t_end) cur = nxt;
     }
+    BCQ_STAMP(6);  // tile loop left
 
     if (split_k && reporter) {  // drain: two tiles may still be in the pipeline
         if (held_tile >= 0) {
@@ -279,6 +329,15 @@ __global__ __launch_bounds__(NW * 64) void bcq_gemv_kernel(GemvParams p)
             complete_row(p, pend_tile * kTileRows + rep_row, pend_old + pend_mine);
         }
     }
+#ifdef BCQ_TRACE
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    BCQ_STAMP(7);  // last atomic returned, last store acknowledged
+    if (p.trace && lane == 0) {
+        unsigned *dst = p.trace + ((size_t)blockIdx.x * NW + wave) * kTraceSlots;
+#pragma unroll
+        for (int i = 0; i < kTraceSlots; ++i) dst[i] = ts[i];
+    }
+#endif
 }
 
 // ---------------------------------------------------------------------------------
@@ -334,20 +393,32 @@ static hipError_t launch_qz(const GemvParams &p, int waves, int sub, int groups,
     return waves == 8 ? launch_one<Q, Z, 8, 1>(p, groups, stream) : launch_one<Q, Z, 4, 1>(p, groups, stream);
 }
 
-hipError_t launch_gemv(const Geom &g, const void *packed, const uint16_t *x, uint16_t *y,
-                       void *workspace, const GemvTuning &t, hipStream_t stream)
+// The launch shape: workgroups, waves per workgroup, start-up order.
+void gemv_launch_shape(const Geom &g, const GemvTuning &t, int *groups_out, int *waves_out, bool *early_out)
 {
-    // 8 waves per workgroup (16 per CU) hide latency better once every wave still gets a tile;
+    // measured: from about four tiles per resident workgroup on, eight waves win (7168 x 7168: 392 workgroups of
+    // 8 waves with one tile each 7.4 us, 512 of 4 waves 8.0 us; 1024 x 8192: 4 waves 4.2 us, 8 waves 4.7 us);
     // the variants with several scaling groups per block exist with 4 waves only
     const long long tiles = (long long)g.nslice * g.ntile;
-    // measured: from about four tiles per resident workgroup on, eight waves win (7168 x 7168: 392 workgroups of
-    // 8 waves with one tile each 7.4 us, 512 of 4 waves 8.0 us; 1024 x 8192: 4 waves 4.2 us, 8 waves 4.7 us)
     const int want = t.waves ? t.waves : (tiles >= 4LL * resident_gemv_groups() ? 8 : 4);
     const int nw = (want == 8 && g.sub == 1) ? 8 : 4;
     int groups = t.workgroups > 0 ? t.workgroups : auto_workgroups(g, nw);
     // at least one workgroup per slice, at most one per row tile of a slice
     if (groups < g.nslice) groups = g.nslice;
-    if ((long long)groups > (long long)g.nslice * g.ntile) groups = g.nslice * g.ntile;
+    if ((long long)groups > tiles) groups = (int)tiles;
+    // one tile per wave at most: the early table build pays (measured: 7168 x 7168 8.0 -> 7.4 us, 8192 x 8192
+    // 8.55 -> 8.3 us, 1024 x 8192 5.0 -> 4.2 us; with more tiles per wave it loses 1.5-2 us on the large layers)
+    *early_out = t.early ? t.early == 1 : tiles <= (long long)groups * nw;
+    *groups_out = groups;
+    *waves_out = nw;
+}
+
+hipError_t launch_gemv(const Geom &g, const void *packed, const uint16_t *x, uint16_t *y,
+                       void *workspace, const GemvTuning &t, hipStream_t stream)
+{
+    int groups, nw;
+    bool early;
+    gemv_launch_shape(g, t, &groups, &nw, &early);
     GemvParams p;
     p.parts = groups / g.nslice;
     p.big_slices = groups % g.nslice;
@@ -359,9 +430,9 @@ hipError_t launch_gemv(const Geom &g, const void *packed, const uint16_t *x, uin
     p.ntile = g.ntile; p.nslice = g.nslice;
     p.tile_bytes = g.tile_bytes;
     p.scale_lane_mask = g.scale_lanes - 1;
-    // one tile per wave at most: the early table build pays (measured: 7168 x 7168 8.0 -> 7.4 us, 8192 x 8192
-    // 8.55 -> 8.3 us, 1024 x 8192 5.0 -> 4.2 us; with more tiles per wave it loses 1.5-2 us on the large layers)
-    const bool early = t.early ? t.early == 1 : tiles <= (long long)groups * nw;
+#ifdef BCQ_TRACE
+    p.trace = static_cast<unsigned *>(t.trace);
+#endif
     const int key = g.q * 2 + g.z;
     switch (key) {
         case 2: return launch_qz<1, 0>(p, nw, g.sub, groups, early, stream);

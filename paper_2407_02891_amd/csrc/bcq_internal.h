@@ -39,6 +39,7 @@ struct GemvTuning {
     int workgroups = 0; // grid size
     int waves = 0;      // waves per workgroup: 4 or 8
     int early = 0;      // GEMV: 1 = build the tables before the first tile has arrived, 2 = never, 0 = automatic
+    void *trace = nullptr;  // tracing build only: DEVICE buffer of kTraceSlots words per wave of the grid
     int skinny_parts = 0;  // K split of the skinny kernel
     int skinny_version = 0;    // 1 = the first skinny kernel (alpha folded into A) also where the second applies
     int skinny_lds_steps = 0;  // second skinny kernel: MFMA steps per block whose A operand comes from the
@@ -57,6 +58,11 @@ constexpr int kStaticScratchRows = 131072;
 hipError_t static_scratch(void **ptr);
 
 constexpr int kProbeBlocks = 512;  // the GEMV's grid: two workgroups per CU
+
+constexpr int kTraceSlots = 16;  // words per wave in the tracing build's timeline buffer
+
+// Launch shape of the GEMV for a layer under given overrides (what launch_gemv will use).
+void gemv_launch_shape(const Geom &g, const GemvTuning &tuning, int *workgroups, int *waves, bool *early);
 
 // Grid size the GEMV uses when none is forced.
 int auto_workgroups(const Geom &g, int waves_per_group);
