@@ -64,6 +64,23 @@ __device__ __forceinline__ void load_tile_buf(TileRegs<Q, Z, SUB> &r, __amdgpu_b
         r.scales[c] = __builtin_amdgcn_raw_buffer_load_b32(rsrc, so + 4u * c, 0, kNonTemporal);
 }
 
+// One piece of the same requests: piece k < 2 Q is sign plane k (row half k div Q, plane k mod Q), piece
+// 2 Q the scale record.  For kernels that spread the requests over their compute steps.
+template <int Q, int Z, int SUB>
+__device__ __forceinline__ void load_tile_piece(TileRegs<Q, Z, SUB> &r, __amdgpu_buffer_rsrc_t rsrc, int lane,
+                                                int scale_lane, int piece)
+{
+    constexpr int kNonTemporal = 2;
+    if (piece < 2 * Q) {
+        r.planes[piece / Q][piece % Q] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, 16u * lane + piece * 1024u, 0, kNonTemporal);
+    } else {
+        const uint32_t so = 2u * Q * 1024u + 4u * (Q + Z) * SUB * scale_lane;
+#pragma unroll
+        for (int c = 0; c < (Q + Z) * SUB; ++c)
+            r.scales[c] = __builtin_amdgcn_raw_buffer_load_b32(rsrc, so + 4u * c, 0, kNonTemporal);
+    }
+}
+
 // binary16 bits of scale c (alpha_0..alpha_{Q-1}, then the offset) of row half t, byte range `range`
 template <int Q, int Z, int SUB>
 __device__ __forceinline__ uint32_t scale_bits_of(const TileRegs<Q, Z, SUB> &r, int t, int range, int c)

@@ -40,6 +40,7 @@ struct GemvTuning {
     int waves = 0;      // waves per workgroup: 4 or 8
     int early = 0;      // GEMV: 1 = build the tables before the first tile has arrived, 2 = never, 0 = automatic
     void *trace = nullptr;  // tracing build only: DEVICE buffer of kTraceSlots words per wave of the grid
+    int trace_groups = 0;   // tracing build, skinny kernel: workgroups that buffer has room for (8 waves each)
     int skinny_parts = 0;  // K split of the skinny kernel
     int skinny_version = 0;    // 1 = the first skinny kernel (alpha folded into A) also where the second applies
     int skinny_lds_steps = 0;  // second skinny kernel: MFMA steps per block whose A operand comes from the

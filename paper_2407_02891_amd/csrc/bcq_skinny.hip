@@ -57,7 +57,28 @@ struct SkinnyParams {
     int units;               // ntg * nslice work units; workgroup w owns units [w*units/G, (w+1)*units/G)
     unsigned tile_bytes;
     int scale_lane_mask;     // 63: one scale record per lane; 15: one per row (group = N)
+#ifdef BCQ_TRACE
+    unsigned *trace;         // [workgroup][wave][kTraceSlots] time stamps (the tracing build only)
+    int trace_groups;        // workgroups the buffer has room for
+#endif
 };
+
+// Per-wave timeline for the tracing build (libbcq_trace.so, see trace_gemv.py): the 100 MHz real-time
+// counter at fixed points and the time spent in each part of a work unit, summed over the wave's units.
+// The normal build compiles none of this.
+#ifdef BCQ_TRACE
+#define BCQ_SK_NOW() ((unsigned)__builtin_amdgcn_s_memrealtime())
+#define BCQ_SK_STAMP(i) (ts[i] = BCQ_SK_NOW())
+#define BCQ_SK_PHASE(i)                 \
+    do {                                \
+        const unsigned now_ = BCQ_SK_NOW(); \
+        ts[i] += now_ - last;           \
+        last = now_;                    \
+    } while (0)
+#else
+#define BCQ_SK_STAMP(i) ((void)0)
+#define BCQ_SK_PHASE(i) ((void)0)
+#endif
 
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -127,18 +148,20 @@ __device__ __forceinline__ void x_slice_store(uint8_t *xs, int tid, const u32x4 
 template <int SUB>
 __device__ __forceinline__ void unrotate(u32x4 &w, int r)
 {
-    if (SUB == 1) {  // chunk = (byte + r) mod 16: rotate the 128-bit ring left by r bytes
-        const int a = r >> 2, b = r & 3;
-        // rotate left by a dwords: t[d] = w[(d - a) & 3]
+    if (SUB == 1) {
+        // chunk = (byte + r) mod 16: rotate the 128-bit ring left by r bytes, i.e. right by k = (16 - r) mod 16:
+        // byte j of the result is byte j + k of w.  Dword step first (two rounds of selects), then one
+        // v_alignbyte_b32 per dword for the k mod 4 bytes that cross dwords.
+        const int k = (16 - r) & 15;
+        const bool s1 = k & 4, s2 = k & 8;
+        const uint32_t b = k & 3;
         uint32_t t0 = w.x, t1 = w.y, t2 = w.z, t3 = w.w;
-        if (a & 2) { uint32_t u0 = t2, u1 = t3, u2 = t0, u3 = t1; t0 = u0; t1 = u1; t2 = u2; t3 = u3; }
-        if (a & 1) { uint32_t u0 = t3, u1 = t0, u2 = t1, u3 = t2; t0 = u0; t1 = u1; t2 = u2; t3 = u3; }
-        // rotate left by b bytes across the 128-bit ring
-        const int sh = 32 - 8 * b;  // 32, 24, 16, 8
-        w.x = (uint32_t)((((unsigned long long)t0 << 32) | t3) >> sh);
-        w.y = (uint32_t)((((unsigned long long)t1 << 32) | t0) >> sh);
-        w.z = (uint32_t)((((unsigned long long)t2 << 32) | t1) >> sh);
-        w.w = (uint32_t)((((unsigned long long)t3 << 32) | t2) >> sh);
+        const uint32_t u0 = s1 ? t1 : t0, u1 = s1 ? t2 : t1, u2 = s1 ? t3 : t2, u3 = s1 ? t0 : t3;
+        t0 = s2 ? u2 : u0; t1 = s2 ? u3 : u1; t2 = s2 ? u0 : u2; t3 = s2 ? u1 : u3;
+        w.x = __builtin_amdgcn_alignbyte(t1, t0, b);
+        w.y = __builtin_amdgcn_alignbyte(t2, t1, b);
+        w.z = __builtin_amdgcn_alignbyte(t3, t2, b);
+        w.w = __builtin_amdgcn_alignbyte(t0, t3, b);
     } else if (SUB == 2) {  // rotate each 64-bit half left by r mod 8 bytes, swap the halves if r >= 8
         unsigned long long lo = ((unsigned long long)w.y << 32) | w.x, hi = ((unsigned long long)w.w << 32) | w.z;
         lo = __builtin_rotateleft64(lo, 8 * (r & 7));
@@ -367,9 +390,14 @@ __device__ __forceinline__ void build_sign_table(uint8_t *tab, int tid)
     }
 }
 
-template <int Q, int Z, int LDS_STEPS, int NB, int TC>
-__device__ __forceinline__ void compute_table(const TileRegs<Q, Z, 1> &cur, const uint8_t *xs_buf, const uint8_t *my_tab,
-                                              int r, int h, f32x4 (&acc)[NB][2])
+// `issue(g)` is called after the MFMAs of step g = 4 B + s (0..15): the kernel uses it to request the next
+// unit's tile and X slice a piece at a time.  Requested all at once at the top of a unit, the 8 waves of a
+// workgroup queue up behind each other in the CU's vector-memory pipeline (measured: up to 1.4 us per unit
+// for the wave that comes last, and everyone waits for it at the barrier).
+template <int Q, int Z, int LDS_STEPS, int NB, int TC, class Issue>
+__device__ __forceinline__ void compute_table(const TileRegs<Q, Z, 1> &cur, const uint8_t *xs_buf, const uint8_t *tab,
+                                              uint32_t copy_bits, int r, int h, f32x4 (&acc)[NB][2], unsigned &t_operands,
+                                              Issue issue)
 {
     // chunk order, then the 4 x 4 dword transpose across the lanes r, r+16, r+32, r+48:
     // wb[t][i][B] = chunks 4h .. 4h+3 of (row 16t + r, block B, plane i)
@@ -386,6 +414,12 @@ __device__ __forceinline__ void compute_table(const TileRegs<Q, Z, 1> &cur, cons
             const auto f13 = __builtin_amdgcn_permlane32_swap(e01[1], e23[1], false, false);
             wb[t][i][0] = f02[0]; wb[t][i][1] = f13[0]; wb[t][i][2] = f02[1]; wb[t][i][3] = f13[1];
         }
+#ifdef BCQ_TRACE
+    asm volatile("" : "+v"(wb[1][Q - 1][3]));  // the tile has arrived and is transposed
+    t_operands = BCQ_SK_NOW();
+#else
+    (void)t_operands;
+#endif
     // batch column 16 nb + r of the staged X sits in row 16 nb + r of the buffer
     const uint8_t *xb = xs_buf + r * kXPitch<2> + h * 16;
     const u32x4 ones = {0x3c003c00u, 0x3c003c00u, 0x3c003c00u, 0x3c003c00u};
@@ -398,16 +432,9 @@ __device__ __forceinline__ void compute_table(const TileRegs<Q, Z, 1> &cur, cons
 #pragma unroll
             for (int e = 0; e < Q + Z; ++e)
                 sc[j][e] = (uint32_t)__builtin_amdgcn_ds_bpermute(4 * (16 * B + 4 * h + j), (int)cur.scales[e]);
-        f32x4 C[NB][2][Q];
+        f32x4 C[NB][2][Q];  // first written by the MFMAs of step 0, whose addend is the constant zero
         f32x4 Cz[NB];
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-            Cz[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int t = 0; t < 2; ++t)
-#pragma unroll
-                for (int i = 0; i < Q; ++i) C[nb][t][i] = f32x4{0.f, 0.f, 0.f, 0.f};
-        }
+        const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
         // The +-1.0 operands of a step serve every group of 16 batch columns.  With four groups a
         // wave runs alone on its SIMD (registers, LDS), so nothing else hides the LDS latency: the
         // operands of step s+1 are requested before the MFMAs of step s are issued (with one or two
@@ -420,8 +447,15 @@ __device__ __forceinline__ void compute_table(const TileRegs<Q, Z, 1> &cur, cons
                 for (int i = 0; i < Q; ++i) {
                     const uint32_t w = wb[t][i][B];
                     if (s < LDS_STEPS) {
-                        const uint32_t byte = (w >> (8 * s)) & 0xffu;
-                        a[t][i] = *reinterpret_cast<const f16x8 *>(my_tab + byte * (16 * TC));
+                        if constexpr (TC == 16) {
+                            // 256 bytes per entry: byte s of w becomes byte 1 of the offset, the lane's copy
+                            // (bits 4..7) byte 0 -- one v_perm_b32 per look-up
+                            const uint32_t off = __builtin_amdgcn_perm(w, copy_bits, 0x0c0c0400u | ((uint32_t)s << 8));
+                            a[t][i] = *reinterpret_cast<const f16x8 *>(tab + off);
+                        } else {
+                            const uint32_t byte = (w >> (8 * s)) & 0xffu;
+                            a[t][i] = *reinterpret_cast<const f16x8 *>(tab + copy_bits + byte * (16 * TC));
+                        }
                     } else {
                         const uint32_t wn = ~w, wn4 = wn >> 4;
                         if (s == 0) a[t][i] = expand_byte<0>(wn, wn4, 0x3c003c00u);
@@ -449,13 +483,15 @@ __device__ __forceinline__ void compute_table(const TileRegs<Q, Z, 1> &cur, cons
                 for (int t = 0; t < 2; ++t)
 #pragma unroll
                     for (int i = 0; i < Q; ++i)
-                        C[nb][t][i] = __builtin_amdgcn_mfma_f32_16x16x32_f16(abuf[cb][t][i], bbuf[cb][nb], C[nb][t][i], 0, 0, 0);
+                        C[nb][t][i] = __builtin_amdgcn_mfma_f32_16x16x32_f16(abuf[cb][t][i], bbuf[cb][nb],
+                                                                             s == 0 ? zero : C[nb][t][i], 0, 0, 0);
                 if (Z)
-                    Cz[nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, ones), bbuf[cb][nb], Cz[nb],
-                                                                    0, 0, 0);
+                    Cz[nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, ones), bbuf[cb][nb],
+                                                                    s == 0 ? zero : Cz[nb], 0, 0, 0);
             }
             if (kPipelined) __builtin_amdgcn_sched_barrier(0);
             else if (s + 1 < 4) fetch(s + 1, abuf[cb ^ 1], bbuf[cb ^ 1]);  // left to the compiler's schedule
+            issue(4 * B + s);
         }
         // acc[nb][t][j] += alpha_i(row 16t + 4h + j, block B) * C[nb][t][i][j]  (+ z * column sums)
 #pragma unroll
@@ -499,6 +535,11 @@ __global__ __launch_bounds__(64 * NW) void bcq_skinny_kernel(SkinnyParams p)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: tile pointers stay in SGPRs
     const int r = lane & 15, h = lane >> 4;
     const int groups = gridDim.x;
+#ifdef BCQ_TRACE
+    unsigned ts[kTraceSlots] = {};
+    unsigned last = 0;
+#endif
+    BCQ_SK_STAMP(0);  // wave started
     const int u_begin = first_unit(blockIdx.x, p.units, groups), u_end = first_unit(blockIdx.x + 1, p.units, groups);
     if (u_begin >= u_end) return;  // uniform for the workgroup, before any barrier
 
@@ -518,7 +559,8 @@ __global__ __launch_bounds__(64 * NW) void bcq_skinny_kernel(SkinnyParams p)
     }
     if (VER == 2) build_sign_table<NT, TC>(tab, tid);
     __syncthreads();
-    const uint8_t *my_tab = tab + (lane & (TC - 1)) * 16;
+    const uint32_t copy_bits = (lane & (TC - 1)) * 16;  // byte offset of this lane's copy inside a table entry
+    BCQ_SK_STAMP(1);  // first X slice staged, sign table built
 
     int buf = 0;
     int u = u_begin;
@@ -532,6 +574,10 @@ __global__ __launch_bounds__(64 * NW) void bcq_skinny_kernel(SkinnyParams p)
         for (int nb = 0; nb < NB; ++nb) acc[nb][0] = acc[nb][1] = f32x4{0.f, 0.f, 0.f, 0.f};
         for (; u < seg_end; ++u) {
             // the next unit of this workgroup, if any (it may be the first of the next segment)
+#ifdef BCQ_TRACE
+            last = BCQ_SK_NOW();
+            ts[15] += 1;
+#endif
             const bool more = u + 1 < u_end;
             int n_slice = slice + 1, n_tg = tg;
             if (n_slice == p.nslice) { n_slice = 0; n_tg = tg + 1; }
@@ -541,17 +587,39 @@ __global__ __launch_bounds__(64 * NW) void bcq_skinny_kernel(SkinnyParams p)
             // none): they stay in flight while this unit is computed
             TileRegs<Q, Z, SUB> nxt;
             u32x4 xr[1024 * NB / NT];
-            load_tile_buf<Q, Z, SUB>(
-                nxt,
-                tile_descriptor(p.blob + ((size_t)n_slice * p.ntile + (n_active ? n_tile : 0)) * p.tile_bytes,
-                                p.tile_bytes, n_active),
-                lane, lane & p.scale_lane_mask);
-            x_slice_load<NB, NT>(p, xrsrc, n_slice, more, tid, xr);
+            const __amdgpu_buffer_rsrc_t n_rsrc = tile_descriptor(
+                p.blob + ((size_t)n_slice * p.ntile + (n_active ? n_tile : 0)) * p.tile_bytes, p.tile_bytes, n_active);
+            // The table kernel spreads these requests over its MFMA steps: the X slice after step 0, two
+            // sign planes after each of the next Q steps, then the scales; the rest of the unit covers
+            // their latency.
+            constexpr bool kSpread = VER == 2;
+            auto issue = [&](int g) {
+                if (g == 0) x_slice_load<NB, NT>(p, xrsrc, n_slice, more, tid, xr);
+                if (g >= 1 && g <= Q) {
+                    load_tile_piece<Q, Z, SUB>(nxt, n_rsrc, lane, lane & p.scale_lane_mask, 2 * (g - 1));
+                    load_tile_piece<Q, Z, SUB>(nxt, n_rsrc, lane, lane & p.scale_lane_mask, 2 * (g - 1) + 1);
+                }
+                if (g == Q + 1) load_tile_piece<Q, Z, SUB>(nxt, n_rsrc, lane, lane & p.scale_lane_mask, 2 * Q);
+            };
+            if (!kSpread || !active) {
+                load_tile_buf<Q, Z, SUB>(nxt, n_rsrc, lane, lane & p.scale_lane_mask);
+                x_slice_load<NB, NT>(p, xrsrc, n_slice, more, tid, xr);
+            }
+            BCQ_SK_PHASE(12);  // top of the unit: addresses of the next one (and its requests, unless spread)
 
             if (active) {
                 if constexpr (VER == 1) compute_folded<Q, Z, SUB, NB>(cur, xs + buf * kBuf, r, h, acc);
-                else compute_table<Q, Z, LDS_STEPS, NB, TC>(cur, xs + buf * kBuf, my_tab, r, h, acc);
+                else {
+                    unsigned t_operands = 0;
+                    compute_table<Q, Z, LDS_STEPS, NB, TC>(cur, xs + buf * kBuf, tab, copy_bits, r, h, acc, t_operands, issue);
+#ifdef BCQ_TRACE
+                    ts[8] += t_operands - last;  // next unit's loads issued, this tile arrived, un-rotated and transposed
+                    last = t_operands;
+                    asm volatile("" : "+v"(acc[0][0][0]), "+v"(acc[0][1][3]));
+#endif
+                }
             }
+            BCQ_SK_PHASE(9);  // the MFMA steps of the unit
             if (!kDouble) __syncthreads();  // everyone done reading the slice that is about to be replaced
             if (more) {
                 x_slice_store<NB, NT, VER>(xs + (kDouble ? (buf ^ 1) * kBuf : 0), tid, xr);
@@ -559,8 +627,11 @@ __global__ __launch_bounds__(64 * NW) void bcq_skinny_kernel(SkinnyParams p)
             }
             tg = n_tg; slice = n_slice; tile = n_tile; active = n_active;
             if (kDouble) buf ^= 1;
+            BCQ_SK_PHASE(10);  // next X slice (waited for and) stored to LDS
             __syncthreads();  // next X slice written (double-buffered: and everyone done with the current one)
+            BCQ_SK_PHASE(11);  // waiting for the other waves at the barrier
         }
+        BCQ_SK_STAMP(2);  // (last) segment's units done
         // this workgroup is done with the tile group: flush (the next segment's first loads are in flight)
         if (seg_active) {
             const int arrivals = owner_of_unit((seg_tg + 1) * p.nslice - 1, p.units, groups) -
@@ -574,6 +645,14 @@ __global__ __launch_bounds__(64 * NW) void bcq_skinny_kernel(SkinnyParams p)
                 skinny_store(p, acc[nb], seg_tile, flush_lane, stage + wave * kStageFloats, arrivals, 16 * nb);
         }
     }
+#ifdef BCQ_TRACE
+    __builtin_amdgcn_s_waitcnt(0);
+    BCQ_SK_STAMP(3);  // last flush done
+    if (p.trace && lane == 0 && (int)blockIdx.x < p.trace_groups) {
+        unsigned *dst = p.trace + ((size_t)blockIdx.x * 8 + wave) * kTraceSlots;  // 8 records per workgroup
+        for (int i = 0; i < kTraceSlots; ++i) dst[i] = ts[i];
+    }
+#endif
 }
 
 // ---------------------------------------------------------------------------------
@@ -665,6 +744,10 @@ hipError_t launch_skinny(const Geom &g, const void *packed, const uint16_t *X, i
     p.ntile = g.ntile; p.nslice = g.nslice; p.ntg = 0; p.units = 0;  // set per kernel (waves per workgroup)
     p.tile_bytes = g.tile_bytes;
     p.scale_lane_mask = g.scale_lanes - 1;
+#ifdef BCQ_TRACE
+    p.trace = static_cast<unsigned *>(tuning.trace);
+    p.trace_groups = tuning.trace_groups;
+#endif
     // forced grid sizes (tuning runs, tests): a K split per tile group, or a plain number of workgroups
     const int parts = tuning.skinny_parts > 0 ? tuning.skinny_parts : -tuning.workgroups;
     const bool single = workspace == nullptr;  // only reachable for a single column slice
