@@ -14,7 +14,8 @@
 //    slice of X (pitch 1040 B: conflict-free ds_read_b128; double-buffered, one barrier per unit).
 //    The units, ordered tile group first, are cut into equal contiguous ranges, one per workgroup,
 //    with as many workgroups as the chip holds at once: every workgroup does the same number of
-//    units (+-1) whatever the shape.  When a range leaves a tile group the accumulators are
+//    units (+-1) whatever the shape.  (Cutting finer, in 128-column blocks, was measured and lost: a
+//    unit done in part still pays its tile, its X slice and its barrier.)  When a range leaves a tile group the accumulators are
 //    flushed; the workgroups that share a tile group are combined with the same fixed-point 64-bit
 //    atomics as in the GEMV (the expected number of arrivals follows from the ranges).
 //  * Tile and X loads go through buffer descriptors (empty / out of range when there is no next
@@ -223,6 +224,7 @@ __device__ __forceinline__ uint32_t scale_bits(const TileRegs<Q, Z, SUB> &t, int
 constexpr int kStagePitch = 33;
 constexpr int kStageFloats = 17 * kStagePitch + 15;  // 576
 
+template <int ROUND>
 __device__ __forceinline__ void skinny_store(const SkinnyParams &p, const f32x4 (&acc)[2], int tile, int lane,
                                              float *stage, int arrivals, int col0)
 {
@@ -244,12 +246,12 @@ __device__ __forceinline__ void skinny_store(const SkinnyParams &p, const f32x4 
         }
         return;
     }
-    // two rounds of four instructions: enough atomics in flight, fewer registers
+    // ROUND atomics in flight at once (8: one round trip to the L2 per flush; 4 where registers are short)
 #pragma unroll
-    for (int k0 = 0; k0 < 8; k0 += 4) {
-        unsigned long long mine[4], old[4];
+    for (int k0 = 0; k0 < 8; k0 += ROUND) {
+        unsigned long long mine[ROUND], old[ROUND];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
+        for (int k = 0; k < ROUND; ++k) {
             const int col = col0 + 2 * (k0 + k) + half;
             mine[k] = encode_partial(v[k0 + k]);
             old[k] = 0;
@@ -258,7 +260,7 @@ __device__ __forceinline__ void skinny_store(const SkinnyParams &p, const f32x4 
                                                 __HIP_MEMORY_SCOPE_AGENT);
         }
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
+        for (int k = 0; k < ROUND; ++k) {
             const int col = col0 + 2 * (k0 + k) + half;
             const unsigned long long total = old[k] + mine[k];
             if (col < p.batch && arrivals_of(total) == (unsigned)arrivals) {
@@ -642,7 +644,7 @@ __global__ __launch_bounds__(64 * NW) void bcq_skinny_kernel(SkinnyParams p)
             asm volatile("" : "+v"(flush_lane));
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb)
-                skinny_store(p, acc[nb], seg_tile, flush_lane, stage + wave * kStageFloats, arrivals, 16 * nb);
+                skinny_store<NB == 1 ? 8 : 4>(p, acc[nb], seg_tile, flush_lane, stage + wave * kStageFloats, arrivals, 16 * nb);
         }
     }
 #ifdef BCQ_TRACE
