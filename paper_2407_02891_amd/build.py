@@ -35,6 +35,24 @@ def build_trace(verbose=False):
     return TRACE_LIB
 
 
+def build_probes(verbose=False):
+    """Compile the stand-alone hardware probes under probes/ (diagnostics; nothing in the library uses them)."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    out = []
+    pdir = os.path.join(HERE, "probes")
+    for f in sorted(os.listdir(pdir)):
+        if not f.endswith(".hip"):
+            continue
+        exe = os.path.join(pdir, f[:-4])
+        cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+               os.path.join(pdir, f), "-o", exe]
+        if verbose:
+            print(" ".join(cmd))
+        subprocess.run(cmd, check=True, stderr=subprocess.DEVNULL if not verbose else None)
+        out.append(exe)
+    return out
+
+
 def kernel_resources(stderr_text):
     """Parse the compiler's kernel-resource-usage remarks: {mangled name: {field: int}}."""
     res, cur = {}, None
@@ -90,4 +108,7 @@ def build(verbose=False, extra_flags=()):
 
 if __name__ == "__main__":
     import sys
-    print(build_trace(verbose=True) if "--trace" in sys.argv else build(verbose=True))
+    if "--probes" in sys.argv:
+        print(build_probes(verbose=True))
+    else:
+        print(build_trace(verbose=True) if "--trace" in sys.argv else build(verbose=True))

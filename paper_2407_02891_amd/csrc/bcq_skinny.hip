@@ -709,14 +709,18 @@ static hipError_t launch_skinny_qz(const SkinnyParams &p, int nb, int parts, boo
 {
     if (sub == 2) return launch_skinny_one<Q, Z, 2, 1, 0, 1>(p, parts, single_slice, stream);
     if (sub == 4) return launch_skinny_one<Q, Z, 4, 1, 0, 1>(p, parts, single_slice, stream);
-    // More than 16 columns: the kernel that folds alpha into A wins (measured 64 / 112 us against
-    // 73 / 124 us for 32 / 64 columns on 7168 x 28672, q = 3): its expansion is shared by the column
-    // groups like the table kernel's, and it needs no per-block accumulators.  Up to 16 columns the
-    // table kernel is a little faster (47.6 against 49.4 us).
-    if (version == 1 || (version == 0 && nb > 1)) {
+    // Which kernel (measured on 7168 x 28672, q = 3, eager launches): up to 16 columns the table kernel (42 against
+    // 55 us for the kernel that folds alpha into A); 17 to 32 columns the table kernel with two column groups and
+    // eight waves where it exists (60 against 70 us), else the alpha-folding kernel; beyond 32 columns the alpha-folding
+    // kernel (118 against 126 us at 64): its expansion is shared by the column groups like the table kernel's, it
+    // needs no per-block accumulators, and the table kernel with four column groups has four waves and 8 table
+    // copies only.
+    const long long tiles = (long long)p.ntile * p.nslice;
+    const bool table2 = nb == 2 && Q + Z <= 3 && (waves == 8 || (waves == 0 && tiles >= 2048));
+    if (version == 1 || (version == 0 && nb > 1 && !table2)) {
         if (nb == 4) return launch_skinny_one<Q, Z, 1, 1, 0, 4>(p, parts, single_slice, stream);
         // 32 columns: eight waves per workgroup from 4096 tiles on (63 against 73 us on 7168 x 28672)
-        if (nb == 2 && (waves == 8 || (waves == 0 && (long long)p.ntile * p.nslice >= 4096)))
+        if (nb == 2 && (waves == 8 || (waves == 0 && tiles >= 4096)))
             return launch_skinny_one<Q, Z, 1, 1, 0, 2, 8>(p, parts, single_slice, stream);
         if (nb == 2) return launch_skinny_one<Q, Z, 1, 1, 0, 2>(p, parts, single_slice, stream);
         return launch_skinny_one<Q, Z, 1, 1, 0, 1>(p, parts, single_slice, stream);
@@ -724,12 +728,18 @@ static hipError_t launch_skinny_qz(const SkinnyParams &p, int nb, int parts, boo
     if constexpr (Q <= 3) {  // with four planes, four column groups do not fit the table kernel's register budget
         if (nb == 4) return launch_skinny_one<Q, Z, 1, 2, 4, 4>(p, parts, single_slice, stream);
     }
+    if constexpr (Q + Z <= 3) {  // three planes plus offset (and four planes) exceed 256 registers with two column groups
+        if (table2) return launch_skinny_one<Q, Z, 1, 2, 4, 2, 8>(p, parts, single_slice, stream);
+    }
     if (nb == 2) return launch_skinny_one<Q, Z, 1, 2, 4, 2>(p, parts, single_slice, stream);
     // all four MFMA steps of a block from the LDS table measured fastest; 3 (one step expanded in
     // registers) is kept as the alternative for tuning runs
-    // Eight waves per workgroup (eight row tiles share one staged slice of X, single-buffered) pay off
-    // on the large layers: 42.5 against 48.0 us on 7168 x 28672, nothing on 9216 x 9216, a loss below.
-    const bool eight = waves == 8 || (waves == 0 && (long long)p.ntile * p.nslice >= 8192);
+    // Eight waves per workgroup (eight row tiles share one staged slice of X; one workgroup per CU, which
+    // leaves LDS for 16 conflict-free table copies) win from about 2000 tiles on (measured at batch 4 / 16,
+    // eager launches: 7168 x 28672 39.4 / 41.4 against 46.0 / 48.1 us, 36864 x 9216 56 / 60 against 67 / 70,
+    // 9216 x 9216 25.1 / 27.2 against 27.5 / 29.2, 7168 x 7168 20.7 / 23.4 against 22.4 / 24.2,
+    // 12288 x 4096 20.9 / 23.1 against 22.3 / 24.0; 4096 x 4096 and below: four waves by 0.4 to 1.5 us).
+    const bool eight = waves == 8 || (waves == 0 && tiles >= 2048);
     if constexpr (Q + Z <= 4) {  // four planes plus offset do not fit the eight-wave kernel's 256 registers
         if (eight && lds_steps != 3) return launch_skinny_one<Q, Z, 1, 2, 4, 1, 8>(p, parts, single_slice, stream);
     }

@@ -351,6 +351,28 @@ def test_skinny_eight_waves_per_workgroup(workgroups, q, offset):
         bcq.set_option("waves", 0)
 
 
+@pytest.mark.parametrize("workgroups", [0, 3, 10])
+@pytest.mark.parametrize("q,offset", [(3, False), (2, True), (1, True), (2, False)])
+def test_skinny_table_kernel_two_column_groups_eight_waves(workgroups, q, offset):
+    """17..32 columns on large layers: the table kernel with two groups of 16 columns and eight waves per
+    workgroup (16 table copies, one X buffer of two groups).  Forced here on small ragged shapes: bit-exact on
+    exact inputs for any work split, workspace left zero, gated on random inputs with ragged batch and rows."""
+    try:
+        bcq.set_option("waves", 8)
+        bcq.set_option("workgroups", workgroups)
+        for batch in (17, 32):
+            L = bcq_synth.make_exact_layer(300, 5120, q, group=128, offset=offset, batch=batch, seed=61 + q + batch)
+            pl = U.upload_and_pack(L, max_batch=batch)
+            expect = ref.gemm(L.planes, L.alpha, L.offset, L.x).astype(np.float16).astype(np.float64)
+            assert np.array_equal(U.gpu_gemm(pl, U.x_dev(L)).astype(np.float64), expect)
+            assert not pl.workspace.cpu().numpy().any()
+        _run_case(203, 3200, q, 128, offset, batch=27, seed=q + workgroups + 5)
+        _run_case(70, 1536, q, 256, offset, batch=18, seed=q + workgroups + 6)
+    finally:
+        bcq.set_option("workgroups", 0)
+        bcq.set_option("waves", 0)
+
+
 @pytest.mark.parametrize("workgroups", [1, 4, 7, 11, 29])
 @pytest.mark.parametrize("version", [1, 2])
 def test_skinny_work_split_does_not_change_results(workgroups, version):
