@@ -93,7 +93,7 @@ def build(verbose=False, extra_flags=()):
     if proc.returncode != 0:
         raise subprocess.CalledProcessError(proc.returncode, cmd)
     res = kernel_resources(proc.stderr)
-    hot = {k: v for k, v in res.items() if "bcq_gemv" in k or "bcq_skinny" in k}
+    hot = {k: v for k, v in res.items() if "bcq_gemv" in k or "bcq_skinny" in k or "bcq_lut4" in k}
     if not hot:
         raise RuntimeError("no resource remarks for the compute kernels: cannot check for spills")
     bad = {k: v for k, v in hot.items()

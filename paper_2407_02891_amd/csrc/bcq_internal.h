@@ -42,7 +42,8 @@ struct GemvTuning {
     void *trace = nullptr;  // tracing build only: DEVICE buffer of kTraceSlots words per wave of the grid
     int trace_groups = 0;   // tracing build, skinny kernel: workgroups that buffer has room for (8 waves each)
     int skinny_parts = 0;  // K split of the skinny kernel
-    int skinny_version = 0;    // 1 = the first skinny kernel (alpha folded into A) also where the second applies
+    int skinny_version = 0;    // 1 = the first skinny kernel (alpha folded into A) also where the second applies,
+                               // 3 = the table kernel for up to four vectors where it applies, 4 = never that one
     int skinny_lds_steps = 0;  // second skinny kernel: MFMA steps per block whose A operand comes from the
                                // LDS table, 3 or 4 (0 = automatic = 4)
 };
@@ -51,6 +52,10 @@ hipError_t launch_gemv(const Geom &g, const void *packed, const uint16_t *x, uin
 // Single-pass kernel for 2 <= batch <= 16 (matrix cores); parts = K split, 0 = automatic.
 hipError_t launch_skinny(const Geom &g, const void *packed, const uint16_t *X, int ldx, uint16_t *Y, int ldy,
                          int batch, void *workspace, const GemvTuning &tuning, hipStream_t stream);
+// Sign-sum tables holding four activation vectors side by side (bcq_lut4.hip): 2 <= batch <= 4.
+bool lut4_applies(const Geom &g, int batch, const void *workspace);
+hipError_t launch_lut4(const Geom &g, const void *packed, const uint16_t *X, int ldx, uint16_t *Y, int ldy, int batch,
+                       void *workspace, const GemvTuning &tuning, hipStream_t stream);
 hipError_t launch_read_probe(const void *buf, size_t bytes, void *sink, hipStream_t stream);
 
 // Rows the file-scope split-K scratch array covers (bcq_gemv_noalloc): 1 MiB per GPU.

@@ -750,6 +750,15 @@ static hipError_t launch_skinny_qz(const SkinnyParams &p, int nb, int parts, boo
 hipError_t launch_skinny(const Geom &g, const void *packed, const uint16_t *X, int ldx, uint16_t *Y, int ldy,
                          int batch, void *workspace, const GemvTuning &tuning, hipStream_t stream)
 {
+    // Up to four vectors, three or four planes, large layers: sign-sum tables with the four sums side by side
+    // (bcq_lut4.hip).  Measured against the matrix-core kernel, q = 3, batch 2 / 4: 7168 x 28672 31.7 / 33.0 against
+    // 34.4 / 35.1 us, 36864 x 9216 41.9 / 42.5 against 55.3 / 49.1, 9216 x 36864 42.3 / 43.7 against 53.1 / 49.7,
+    // 28672 x 8192 33.3 / 34.5 against 38.3 / 35.8; it loses below about 12000 tiles (9216 x 9216: 21.7 / 24.5 against
+    // 19.0 / 19.7) and with one or two planes (its table builds and barriers do not shrink with q).
+    if (lut4_applies(g, batch, workspace) &&
+        (tuning.skinny_version == 3 ||
+         (tuning.skinny_version == 0 && g.q >= 3 && (long long)g.ntile * g.nslice >= 12288)))
+        return launch_lut4(g, packed, X, ldx, Y, ldy, batch, workspace, tuning, stream);
     SkinnyParams p;
     p.blob = static_cast<const uint8_t *>(packed);
     p.M = g.M; p.N = g.N; p.Mp = g.Mp; p.ldx = ldx; p.ldy = ldy;

@@ -373,6 +373,41 @@ def test_skinny_table_kernel_two_column_groups_eight_waves(workgroups, q, offset
         bcq.set_option("waves", 0)
 
 
+@pytest.mark.parametrize("workgroups", [0, 1, 3, 7])
+@pytest.mark.parametrize("batch", [2, 3, 4])
+def test_table_kernel_for_up_to_four_vectors(workgroups, batch):
+    """2..4 activation vectors on large layers: sign-sum tables with the four sums side by side, rebuilt along K
+    (bcq_lut4.hip).  Forced here on small shapes: ragged rows and columns (a last half slice that is empty or
+    partial), fewer tiles than a row group has, one to four planes with and without offset, row-wise scales, any
+    work split; bit for bit the oracle's result (one binary16 rounding) on exact inputs, workspace left zero;
+    gate on random inputs with outlier channels; padded rows of X and Y."""
+    try:
+        bcq.set_option("skinny_version", 3)
+        bcq.set_option("workgroups", workgroups)
+        for (M, N, q, off, group) in [(96, 2048, 3, False, 128), (300, 5120, 3, True, 128), (70, 1536, 2, True, 128),
+                                      (1000, 2560, 1, False, 128), (203, 3200, 4, False, 128), (96, 2048, 3, True, 2048),
+                                      (40, 1024, 2, False, 256), (2100, 1024, 3, False, 128)]:
+            L = bcq_synth.make_exact_layer(M, N, q, group=group, offset=off, batch=batch, seed=M + q + batch)
+            pl = U.upload_and_pack(L, max_batch=batch)
+            expect = ref.gemm(L.planes, L.alpha, L.offset, L.x).astype(np.float16).astype(np.float64)
+            assert np.array_equal(U.gpu_gemm(pl, U.x_dev(L)).astype(np.float64), expect), (M, N, q, off, group)
+            assert not pl.workspace.cpu().numpy().any()
+        _run_case(600, 4608, 3, 128, True, batch=batch, seed=batch + workgroups, outlier_frac=0.01)
+        L = bcq_synth.make_exact_layer(150, 3072, 3, group=128, offset=True, batch=batch, seed=77)
+        pl = U.upload_and_pack(L, max_batch=batch)
+        expect = ref.gemm(L.planes, L.alpha, L.offset, L.x).astype(np.float16).astype(np.float64)
+        X = torch.zeros((batch, L.N + 64), dtype=torch.float16, device="cuda")
+        X[:, :L.N] = U.x_dev(L)
+        Y = torch.full((batch, L.M + 10), 3.0, dtype=torch.float16, device="cuda")
+        bcq.gemm_skinny(pl.desc, pl.packed, X, X.stride(0), Y, Y.stride(0), batch, pl.workspace)
+        torch.cuda.synchronize()
+        assert np.array_equal(Y[:, :L.M].cpu().numpy().astype(np.float64), expect)
+        assert torch.all(Y[:, L.M:] == 3.0)
+    finally:
+        bcq.set_option("workgroups", 0)
+        bcq.set_option("skinny_version", 0)
+
+
 @pytest.mark.parametrize("workgroups", [1, 4, 7, 11, 29])
 @pytest.mark.parametrize("version", [1, 2])
 def test_skinny_work_split_does_not_change_results(workgroups, version):
