@@ -119,6 +119,37 @@ def test_compensation_lowers_the_output_error():
     assert np.mean(e_gptq < e_rtn) > 0.7
 
 
+def test_output_error_is_the_squared_error_of_the_layer_outputs():
+    """Eq. 5's criterion, read as the row's output error: output_error (evaluated through H = 2 X X^T) equals
+    || w_hat X - w X ||^2 computed on the calibration inputs themselves, row by row."""
+    W, X = _layer(7, 24, 96, 11)
+    rng = np.random.default_rng(12)
+    n = 3
+    S = rng.uniform(0.01, 0.05, size=7)
+    b = rng.uniform(-0.2, 0.0, size=7)
+    Wq = rng.integers(0, 2 ** n, size=W.shape).astype(np.float64)
+    e = Q.output_error(W, Wq, S, b, Q.hessian(X))
+    for m in range(7):
+        w_hat = S[m] * Wq[m] + b[m]
+        direct = sum((w_hat @ X[:, t] - W[m] @ X[:, t]) ** 2 for t in range(X.shape[1]))
+        assert np.isclose(e[m], direct, rtol=1e-10, atol=0.0)
+    assert np.all(Q.output_error(W, (W - b[:, None]) / S[:, None], S, b, Q.hessian(X)) < 1e-20)  # w_hat = w: no error
+
+
+def test_cholesky_factor_is_the_upper_factor_of_the_dampened_inverse():
+    """U of the GPTQ pass: upper triangular with positive diagonal, U^T U (H + damp mean(diag H) I) = I;
+    damp = 0 on a diagonal H gives diag(1 / sqrt(h))."""
+    _, X = _layer(1, 20, 64, 13)
+    H = Q.hessian(X)
+    for damp in (0.01, 0.25):
+        U = Q.cholesky_factor(H, damp)
+        assert np.allclose(U, np.triu(U)) and np.all(np.diag(U) > 0)
+        Hd = H + damp * np.mean(np.diag(H)) * np.eye(20)
+        assert np.allclose(U.T @ U @ Hd, np.eye(20), atol=1e-9)
+    h = np.array([4.0, 0.25, 9.0])
+    assert np.allclose(Q.cholesky_factor(np.diag(h), 0.0), np.diag(1.0 / np.sqrt(h)))
+
+
 def test_search_then_fuse_round_trip():
     """The searched parameters feed oracle.fuse unchanged: dequantising the fused planes gives
     S W_q + qbias for every row's own tied-plane set."""
