@@ -154,6 +154,20 @@ __device__ __forceinline__ float sum_block_owners(float a0, float a1)
     return __uint_as_float(r0) + __uint_as_float(r1);
 }
 
+// Work split of the kernels that walk along K (bcq_skinny.hip, bcq_lut4.hip): `units` items are cut into `groups`
+// contiguous ranges of floor/ceil(units / groups).  First item of workgroup w, and the workgroup that owns item u.
+__device__ __forceinline__ int first_unit(int w, int units, int groups)
+{
+    return (int)(((long long)w * units) / groups);
+}
+
+__device__ __forceinline__ int owner_of_unit(int u, int units, int groups)
+{
+    return (int)((((long long)u + 1) * groups - 1) / units);
+}
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
 __device__ __forceinline__ unsigned arrivals_of(unsigned long long total)
 {
     return static_cast<unsigned>(total) & ((1u << kCountBits) - 1u);

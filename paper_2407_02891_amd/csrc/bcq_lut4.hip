@@ -43,18 +43,10 @@ struct Lut4Params {
     int scale_lane_mask;  // 63: one scale record per lane; 15: one per row (group = N)
 };
 
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-
 constexpr int kLutWaves = 16;
 constexpr int kLutTilesPerGroup = 2 * kLutWaves;
 constexpr int kHalfCols = kTileCols / 2;  // 256
 constexpr uint32_t kLutNoTile = 0xfff00000u;  // offset of "no such tile"; blobs must be smaller
-
-__device__ __forceinline__ int lut_first_unit(int w, int units, int groups) { return (int)(((long long)w * units) / groups); }
-__device__ __forceinline__ int lut_owner_of_unit(int u, int units, int groups)
-{
-    return (int)((((long long)u + 1) * groups - 1) / units);
-}
 
 // Byte offset in the blob of (slice, tile), or of "no such tile": beyond every blob this kernel accepts and far
 // enough from 2^32 for the offsets added to it not to wrap, so that the loads return zeros.
@@ -87,7 +79,7 @@ __global__ __launch_bounds__(64 * kLutWaves) void bcq_lut4_kernel(Lut4Params p)
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int groups = gridDim.x;
-    const int u_begin = lut_first_unit(blockIdx.x, p.units, groups), u_end = lut_first_unit(blockIdx.x + 1, p.units, groups);
+    const int u_begin = first_unit(blockIdx.x, p.units, groups), u_end = first_unit(blockIdx.x + 1, p.units, groups);
     if (u_begin >= u_end) return;  // uniform for the workgroup, before any barrier
     const int nh = 2 * p.nslice;   // half slices per row group
 
@@ -228,7 +220,7 @@ __global__ __launch_bounds__(64 * kLutWaves) void bcq_lut4_kernel(Lut4Params p)
             __syncthreads();  // everyone done with these tables; next activations parked
         }
         // ---- this workgroup is done with the row group: combine the two blocks of a row, then flush
-        const int arrivals = lut_owner_of_unit((seg_rg + 1) * nh - 1, p.units, groups) - lut_owner_of_unit(seg_rg * nh, p.units, groups) + 1;
+        const int arrivals = owner_of_unit((seg_rg + 1) * nh - 1, p.units, groups) - owner_of_unit(seg_rg * nh, p.units, groups) + 1;
         // (the lane index is passed through an empty asm so that the per-lane address arithmetic of the flush is
         // not hoisted out of the outer loop into registers that stay live during the units)
         int flush_lane = lane;

@@ -82,7 +82,6 @@ struct SkinnyParams {
 #endif
 
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 // Staged X in LDS: one row of 64 chunks (16 B each) per batch column, rows `pitch` bytes apart.  A
 // ds_read_b128 is served 16 lanes at a time -- lanes {0-3, 12-15, 20-23, 24-27}, {4-7, 8-11, 16-19,
@@ -270,18 +269,6 @@ __device__ __forceinline__ void skinny_store(const SkinnyParams &p, const f32x4 
             }
         }
     }
-}
-
-// First unit of workgroup w, and the workgroup that owns unit u, for `units` units cut into `groups`
-// contiguous ranges of floor/ceil(units / groups).
-__device__ __forceinline__ int first_unit(int w, int units, int groups)
-{
-    return (int)(((long long)w * units) / groups);
-}
-
-__device__ __forceinline__ int owner_of_unit(int u, int units, int groups)
-{
-    return (int)((((long long)u + 1) * groups - 1) / units);
 }
 
 // ---------------------------------------------------------------------------------
