@@ -139,7 +139,10 @@ __device__ __forceinline__ void x_slice_store(uint8_t *xs, int tid, const u32x4 
         o.w = __builtin_amdgcn_perm(v.w, v.y, 0x07060302u);  // (x3, x7)
         // VER 2: chunk 4 h + s of a block sits at position 4 s + h
         const int pos = VER == 2 ? ((chunk & 48) | ((chunk & 3) << 2) | ((chunk >> 2) & 3)) : chunk;
-        *reinterpret_cast<u32x4 *>(xs + c * kXPitch<VER> + pos * 16) = o;
+        // VER 2: batch column h + 4 j of a group of 16 goes to row 4 h + j, so that the lanes 16 h + r of the (transposed)
+        // MFMA result hold the columns h, h + 4, h + 8, h + 12: a flush instruction then covers four neighbouring columns
+        const int row = VER == 2 ? ((c & ~15) | ((c & 3) << 2) | ((c >> 2) & 3)) : c;
+        *reinterpret_cast<u32x4 *>(xs + row * kXPitch<VER> + pos * 16) = o;
     }
 }
 
@@ -223,15 +226,19 @@ __device__ __forceinline__ uint32_t scale_bits(const TileRegs<Q, Z, SUB> &t, int
 constexpr int kStagePitch = 33;
 constexpr int kStageFloats = 17 * kStagePitch + 15;  // 576
 
-template <int ROUND>
+template <int ROUND, bool TRANSPOSED>
 __device__ __forceinline__ void skinny_store(const SkinnyParams &p, const f32x4 (&acc)[2], int tile, int lane,
                                              float *stage, int arrivals, int col0)
 {
     const int r = lane & 15, h = lane >> 4;
+    // acc[t][i] is (row 16t + 4h + i, column r) of the tile, or with TRANSPOSED (row 16t + r, column h + 4i)
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) stage[r * kStagePitch + 16 * t + 4 * h + i] = acc[t][i];
+        for (int i = 0; i < 4; ++i) {
+            if (TRANSPOSED) stage[(h + 4 * i) * kStagePitch + 16 * t + r] = acc[t][i];
+            else stage[r * kStagePitch + 16 * t + 4 * h + i] = acc[t][i];
+        }
     // same wave: its LDS operations complete in order, no barrier needed
     const int row = tile * kTileRows + (lane & 31), half = lane >> 5;
     float v[8];
@@ -261,6 +268,47 @@ __device__ __forceinline__ void skinny_store(const SkinnyParams &p, const f32x4 
 #pragma unroll
         for (int k = 0; k < ROUND; ++k) {
             const int col = col0 + 2 * (k0 + k) + half;
+            const unsigned long long total = old[k] + mine[k];
+            if (col < p.batch && arrivals_of(total) == (unsigned)arrivals) {
+                if (row < p.M) p.Y[(size_t)col * p.ldy + row] = float_to_half_bits(decode_total(total));
+                __hip_atomic_store(p.accum + (size_t)col * p.Mp + row, 0ull, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+    }
+}
+
+// The same for accumulators held transposed (the table kernel): acc[t][j] = (batch column col0 + h + 4j, row 16t + r)
+// of the tile, lane 16h + r.  No turn through LDS: an instruction's lanes cover 16 consecutive rows of four neighbouring
+// columns, and with few columns the instructions for j beyond them have no active lane.
+template <int ROUND>
+__device__ __forceinline__ void skinny_store_transposed(const SkinnyParams &p, const f32x4 (&acc)[2], int tile, int lane,
+                                                        int arrivals, int col0)
+{
+    const int r = lane & 15, h = lane >> 4;
+    if (arrivals == 1) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int col = col0 + h + 4 * (k & 3), row = tile * kTileRows + 16 * (k >> 2) + r;
+            if (col < p.batch && row < p.M) p.Y[(size_t)col * p.ldy + row] = float_to_half_bits(acc[k >> 2][k & 3]);
+        }
+        return;
+    }
+#pragma unroll
+    for (int k0 = 0; k0 < 8; k0 += ROUND) {
+        unsigned long long mine[ROUND], old[ROUND];
+#pragma unroll
+        for (int k = 0; k < ROUND; ++k) {
+            const int col = col0 + h + 4 * ((k0 + k) & 3), row = tile * kTileRows + 16 * ((k0 + k) >> 2) + r;
+            mine[k] = encode_partial(acc[(k0 + k) >> 2][(k0 + k) & 3]);
+            old[k] = 0;
+            if (col < p.batch)
+                old[k] = __hip_atomic_fetch_add(p.accum + (size_t)col * p.Mp + row, mine[k], __ATOMIC_RELAXED,
+                                                __HIP_MEMORY_SCOPE_AGENT);
+        }
+#pragma unroll
+        for (int k = 0; k < ROUND; ++k) {
+            const int col = col0 + h + 4 * ((k0 + k) & 3), row = tile * kTileRows + 16 * ((k0 + k) >> 2) + r;
             const unsigned long long total = old[k] + mine[k];
             if (col < p.batch && arrivals_of(total) == (unsigned)arrivals) {
                 if (row < p.M) p.Y[(size_t)col * p.ldy + row] = float_to_half_bits(decode_total(total));
@@ -409,18 +457,24 @@ __device__ __forceinline__ void compute_table(const TileRegs<Q, Z, 1> &cur, cons
 #else
     (void)t_operands;
 #endif
+    // The products are formed transposed (batch columns as the rows of the MFMA result): lane 16 h + r then holds four
+    // batch columns (h + 4 j, see x_slice_store) of weight row r, whose scales for block B sit in lane 16 B + r.  One copy of every
+    // lane group's scale record in every lane group: three lane-swap instructions per dword, once per unit.
+    uint32_t sc[4][Q + Z];
+#pragma unroll
+    for (int e = 0; e < Q + Z; ++e) {
+        const uint32_t v = cur.scales[e];
+        const auto lo_hi = __builtin_amdgcn_permlane32_swap(v, v, false, false);  // lane groups (0,1,0,1), (2,3,2,3)
+        const unsigned lo = lo_hi[0], hi = lo_hi[1];
+        const auto g01 = __builtin_amdgcn_permlane16_swap(lo, lo, false, false);  // (0,0,0,0), (1,1,1,1)
+        const auto g23 = __builtin_amdgcn_permlane16_swap(hi, hi, false, false);  // (2,2,2,2), (3,3,3,3)
+        sc[0][e] = g01[0]; sc[1][e] = g01[1]; sc[2][e] = g23[0]; sc[3][e] = g23[1];
+    }
     // batch column 16 nb + r of the staged X sits in row 16 nb + r of the buffer
     const uint8_t *xb = xs_buf + r * kXPitch<2> + h * 16;
     const u32x4 ones = {0x3c003c00u, 0x3c003c00u, 0x3c003c00u, 0x3c003c00u};
 #pragma unroll
     for (int B = 0; B < 4; ++B) {
-        // scales of rows 4h + j of this block, held by lanes 16 B + 4h + j, into this lane
-        uint32_t sc[4][Q + Z];
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int e = 0; e < Q + Z; ++e)
-                sc[j][e] = (uint32_t)__builtin_amdgcn_ds_bpermute(4 * (16 * B + 4 * h + j), (int)cur.scales[e]);
         f32x4 C[NB][2][Q];  // first written by the MFMAs of step 0, whose addend is the constant zero
         f32x4 Cz[NB];
         const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
@@ -472,30 +526,29 @@ __device__ __forceinline__ void compute_table(const TileRegs<Q, Z, 1> &cur, cons
                 for (int t = 0; t < 2; ++t)
 #pragma unroll
                     for (int i = 0; i < Q; ++i)
-                        C[nb][t][i] = __builtin_amdgcn_mfma_f32_16x16x32_f16(abuf[cb][t][i], bbuf[cb][nb],
+                        C[nb][t][i] = __builtin_amdgcn_mfma_f32_16x16x32_f16(bbuf[cb][nb], abuf[cb][t][i],
                                                                              s == 0 ? zero : C[nb][t][i], 0, 0, 0);
                 if (Z)
-                    Cz[nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, ones), bbuf[cb][nb],
+                    Cz[nb] = __builtin_amdgcn_mfma_f32_16x16x32_f16(bbuf[cb][nb], __builtin_bit_cast(f16x8, ones),
                                                                     s == 0 ? zero : Cz[nb], 0, 0, 0);
             }
             if (kPipelined) __builtin_amdgcn_sched_barrier(0);
             else if (s + 1 < 4) fetch(s + 1, abuf[cb ^ 1], bbuf[cb ^ 1]);  // left to the compiler's schedule
             issue(4 * B + s);
         }
-        // acc[nb][t][j] += alpha_i(row 16t + 4h + j, block B) * C[nb][t][i][j]  (+ z * column sums)
+        // acc[nb][t][j] (batch column 16 nb + h + 4j, row 16t + r) += alpha_i(row, block B) * C[nb][t][i][j]  (+ z * column sums)
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
+            for (int c = 0; c < Q + Z; ++c) {
+                const int e = t * (Q + Z) + c;  // half index in the scale record
+                const uint32_t pair = sc[B][e >> 1];
+                const float v = half_bits_to_float((e & 1) ? (pair >> 16) : (pair & 0xffffu));
 #pragma unroll
-                for (int c = 0; c < Q + Z; ++c) {
-                    const int e = t * (Q + Z) + c;  // half index in the lane's scale record
-                    const uint32_t pair = sc[j][e >> 1];
-                    const float v = half_bits_to_float((e & 1) ? (pair >> 16) : (pair & 0xffffu));
+                for (int j = 0; j < 4; ++j)
 #pragma unroll
                     for (int nb = 0; nb < NB; ++nb)
                         acc[nb][t][j] = fmaf(v, c < Q ? C[nb][t][c < Q ? c : 0][j] : Cz[nb][j], acc[nb][t][j]);
-                }
             }
     }
 }
@@ -518,7 +571,7 @@ __global__ __launch_bounds__(64 * NW) void bcq_skinny_kernel(SkinnyParams p)
     constexpr int kBuf = NB * kXBuf<VER>;
     __shared__ __attribute__((aligned(16))) uint8_t xs[(kDouble ? 2 : 1) * kBuf];
     __shared__ __attribute__((aligned(16))) uint8_t tab[VER == 2 ? kTabBytes<TC> : 16];
-    __shared__ float stage[NW * kStageFloats];
+    __shared__ float stage[VER == 2 && NB < 4 ? 1 : NW * kStageFloats];  // (the direct flush does not turn its results through LDS)
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: tile pointers stay in SGPRs
@@ -630,8 +683,13 @@ __global__ __launch_bounds__(64 * NW) void bcq_skinny_kernel(SkinnyParams p)
             int flush_lane = lane;
             asm volatile("" : "+v"(flush_lane));
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb)
-                skinny_store<NB == 1 ? 8 : 4>(p, acc[nb], seg_tile, flush_lane, stage + wave * kStageFloats, arrivals, 16 * nb);
+            for (int nb = 0; nb < NB; ++nb) {
+                // (four column groups: the kernel has no scalar registers left for the direct form's column tests)
+                if constexpr (VER == 2 && NB < 4)
+                    skinny_store_transposed<NB == 1 ? 8 : 4>(p, acc[nb], seg_tile, flush_lane, arrivals, 16 * nb);
+                else
+                    skinny_store<NB == 1 ? 8 : 4, VER == 2>(p, acc[nb], seg_tile, flush_lane, stage + wave * kStageFloats, arrivals, 16 * nb);
+            }
         }
     }
 #ifdef BCQ_TRACE
@@ -738,13 +796,15 @@ hipError_t launch_skinny(const Geom &g, const void *packed, const uint16_t *X, i
                          int batch, void *workspace, const GemvTuning &tuning, hipStream_t stream)
 {
     // Up to four vectors, three or four planes, large layers: sign-sum tables with the four sums side by side
-    // (bcq_lut4.hip).  Measured against the matrix-core kernel, q = 3, batch 2 / 4: 7168 x 28672 31.7 / 33.0 against
-    // 34.4 / 35.1 us, 36864 x 9216 41.9 / 42.5 against 55.3 / 49.1, 9216 x 36864 42.3 / 43.7 against 53.1 / 49.7,
-    // 28672 x 8192 33.3 / 34.5 against 38.3 / 35.8; it loses below about 12000 tiles (9216 x 9216: 21.7 / 24.5 against
-    // 19.0 / 19.7) and with one or two planes (its table builds and barriers do not shrink with q).
+    // (bcq_lut4.hip).  Measured against the matrix-core kernel, q = 3, batch 2 / 4: 7168 x 28672 31.2 / 32.8 against
+    // 32.4 / 31.8 us, 28672 x 8192 33.2 / 35.5 against 37.4 / 33.7, 36864 x 9216 42.6 / 44.6 against 49.3 / 46.0,
+    // 9216 x 36864 41.9 / 44.5 against 49.4 / 45.9: with two vectors it wins from about 12000 tiles on, with three or
+    // four only on the largest layers; it loses on smaller ones (9216 x 9216: 21.3 / 24.1 against 18.3 / 18.2) and
+    // with one or two planes (its table builds and barriers do not shrink with q).
+    const long long all_tiles = (long long)g.ntile * g.nslice;
     if (lut4_applies(g, batch, workspace) &&
         (tuning.skinny_version == 3 ||
-         (tuning.skinny_version == 0 && g.q >= 3 && (long long)g.ntile * g.nslice >= 12288)))
+         (tuning.skinny_version == 0 && g.q >= 3 && all_tiles >= (batch == 2 ? 12288 : 18432))))
         return launch_lut4(g, packed, X, ldx, Y, ldy, batch, workspace, tuning, stream);
     SkinnyParams p;
     p.blob = static_cast<const uint8_t *>(packed);
