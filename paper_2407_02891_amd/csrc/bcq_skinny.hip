@@ -761,7 +761,7 @@ static hipError_t launch_skinny_qz(const SkinnyParams &p, int nb, int parts, boo
     // needs no per-block accumulators, and the table kernel with four column groups has four waves and 8 table
     // copies only.
     const long long tiles = (long long)p.ntile * p.nslice;
-    const bool table2 = nb == 2 && Q + Z <= 3 && (waves == 8 || (waves == 0 && tiles >= 2048));
+    const bool table2 = nb == 2 && Q <= 3 && (waves == 8 || (waves == 0 && tiles >= 2048));
     if (version == 1 || (version == 0 && nb > 1 && !table2)) {
         if (nb == 4) return launch_skinny_one<Q, Z, 1, 1, 0, 4>(p, parts, single_slice, stream);
         // 32 columns: eight waves per workgroup from 4096 tiles on (63 against 73 us on 7168 x 28672)
@@ -773,7 +773,7 @@ static hipError_t launch_skinny_qz(const SkinnyParams &p, int nb, int parts, boo
     if constexpr (Q <= 3) {  // with four planes, four column groups do not fit the table kernel's register budget
         if (nb == 4) return launch_skinny_one<Q, Z, 1, 2, 4, 4>(p, parts, single_slice, stream);
     }
-    if constexpr (Q + Z <= 3) {  // three planes plus offset (and four planes) exceed 256 registers with two column groups
+    if constexpr (Q <= 3) {  // four planes exceed 256 registers with two column groups and eight waves
         if (table2) return launch_skinny_one<Q, Z, 1, 2, 4, 2, 8>(p, parts, single_slice, stream);
     }
     if (nb == 2) return launch_skinny_one<Q, Z, 1, 2, 4, 2>(p, parts, single_slice, stream);
@@ -785,9 +785,7 @@ static hipError_t launch_skinny_qz(const SkinnyParams &p, int nb, int parts, boo
     // 9216 x 9216 25.1 / 27.2 against 27.5 / 29.2, 7168 x 7168 20.7 / 23.4 against 22.4 / 24.2,
     // 12288 x 4096 20.9 / 23.1 against 22.3 / 24.0; 4096 x 4096 and below: four waves by 0.4 to 1.5 us).
     const bool eight = waves == 8 || (waves == 0 && tiles >= 2048);
-    if constexpr (Q + Z <= 4) {  // four planes plus offset do not fit the eight-wave kernel's 256 registers
-        if (eight && lds_steps != 3) return launch_skinny_one<Q, Z, 1, 2, 4, 1, 8>(p, parts, single_slice, stream);
-    }
+    if (eight && lds_steps != 3) return launch_skinny_one<Q, Z, 1, 2, 4, 1, 8>(p, parts, single_slice, stream);
     return lds_steps == 3 ? launch_skinny_one<Q, Z, 1, 2, 3, 1>(p, parts, single_slice, stream)
                           : launch_skinny_one<Q, Z, 1, 2, 4, 1>(p, parts, single_slice, stream);
 }

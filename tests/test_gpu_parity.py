@@ -352,11 +352,12 @@ def test_skinny_eight_waves_per_workgroup(workgroups, q, offset):
 
 
 @pytest.mark.parametrize("workgroups", [0, 3, 10])
-@pytest.mark.parametrize("q,offset", [(3, False), (2, True), (1, True), (2, False)])
+@pytest.mark.parametrize("q,offset", [(3, False), (2, True), (1, True), (2, False), (3, True), (4, False)])
 def test_skinny_table_kernel_two_column_groups_eight_waves(workgroups, q, offset):
     """17..32 columns on large layers: the table kernel with two groups of 16 columns and eight waves per
-    workgroup (16 table copies, one X buffer of two groups).  Forced here on small ragged shapes: bit-exact on
-    exact inputs for any work split, workspace left zero, gated on random inputs with ragged batch and rows."""
+    workgroup (16 table copies, one X buffer of two groups; up to three planes, four planes take the four-wave
+    kernel).  Forced here on small ragged shapes: bit-exact on exact inputs for any work split, workspace left
+    zero, gated on random inputs with ragged batch and rows."""
     try:
         bcq.set_option("waves", 8)
         bcq.set_option("workgroups", workgroups)
