@@ -154,15 +154,36 @@ __device__ __forceinline__ float sum_block_owners(float a0, float a1)
     return __uint_as_float(r0) + __uint_as_float(r1);
 }
 
-// Work split of the kernels that walk along K (bcq_skinny.hip, bcq_lut4.hip): `units` items are cut into `groups`
-// contiguous ranges of floor/ceil(units / groups).  First item of workgroup w, and the workgroup that owns item u.
-__device__ __forceinline__ int first_unit(int w, int units, int groups)
+// Work split of the kernels that walk along K (bcq_skinny.hip, bcq_lut4.hip): `units` work items are cut into one
+// contiguous range per workgroup, of floor or ceil(units / workgroups) items.  Two ways to place the longer ranges:
+//
+// FRONT (kernels that run one workgroup per compute unit): the first `rem` = units mod workgroups of the workgroups
+// take `base` + 1 = floor(units / workgroups) + 1 items, the others `base`.  The hardware starts the workgroups in
+// order, so the longer ranges begin up to 0.7 us before the last ones (measured: 1 us per launch on a layer with
+// 1.5 items per workgroup).  The host passes base and rem.
+//
+// Otherwise the longer ranges are spread evenly over the workgroup numbers (range w = [floor(w units / groups),
+// floor((w + 1) units / groups))): with two workgroups per compute unit, numbers w and w + groups / 2 typically
+// share one, and the front placement would give some compute units two long ranges (4.6 us on a 45 us launch).  The
+// kernel of bcq_lut4.hip keeps the even spread too: its long ranges placed at the front lie next to each other in
+// memory and cost 2 to 3 us on layers with five or six items per workgroup.
+//
+// First item of workgroup w, and the workgroup that owns item u.
+template <bool FRONT>
+__device__ __forceinline__ int first_unit(int w, int units, int groups, int base, int rem)
 {
+    if (FRONT) return w * base + (w < rem ? w : rem);
     return (int)(((long long)w * units) / groups);
 }
 
-__device__ __forceinline__ int owner_of_unit(int u, int units, int groups)
+template <bool FRONT>
+__device__ __forceinline__ int owner_of_unit(int u, int units, int groups, int base, int rem)
 {
+    if (FRONT) {
+        const int cut = rem * (base + 1);  // items of the longer ranges (base = 0 only if every item is below `cut`)
+        const long long n = u < cut ? u : u - cut, d = u < cut ? base + 1 : base;
+        return (u < cut ? 0 : rem) + (int)(n / d);
+    }
     return (int)((((long long)u + 1) * groups - 1) / units);
 }
 

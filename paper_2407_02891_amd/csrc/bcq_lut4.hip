@@ -78,8 +78,11 @@ __global__ __launch_bounds__(64 * kLutWaves) void bcq_lut4_kernel(Lut4Params p)
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // (the longer ranges spread evenly over the workgroups: placed on the first ones, whose ranges are neighbours in
+    // memory, they cost 2 to 3 us on the layers with five or six units per workgroup)
     const int groups = gridDim.x;
-    const int u_begin = first_unit(blockIdx.x, p.units, groups), u_end = first_unit(blockIdx.x + 1, p.units, groups);
+    const int u_begin = first_unit<false>(blockIdx.x, p.units, groups, 0, 0);
+    const int u_end = first_unit<false>(blockIdx.x + 1, p.units, groups, 0, 0);
     if (u_begin >= u_end) return;  // uniform for the workgroup, before any barrier
     const int nh = 2 * p.nslice;   // half slices per row group
 
@@ -220,7 +223,8 @@ __global__ __launch_bounds__(64 * kLutWaves) void bcq_lut4_kernel(Lut4Params p)
             __syncthreads();  // everyone done with these tables; next activations parked
         }
         // ---- this workgroup is done with the row group: combine the two blocks of a row, then flush
-        const int arrivals = owner_of_unit((seg_rg + 1) * nh - 1, p.units, groups) - owner_of_unit(seg_rg * nh, p.units, groups) + 1;
+        const int arrivals = owner_of_unit<false>((seg_rg + 1) * nh - 1, p.units, groups, 0, 0) -
+                             owner_of_unit<false>(seg_rg * nh, p.units, groups, 0, 0) + 1;
         // (the lane index is passed through an empty asm so that the per-lane address arithmetic of the flush is
         // not hoisted out of the outer loop into registers that stay live during the units)
         int flush_lane = lane;

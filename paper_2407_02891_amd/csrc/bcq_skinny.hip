@@ -55,7 +55,8 @@ struct SkinnyParams {
     unsigned long long *accum;  // [batch][Mp]
     int M, N, Mp, batch, ldx, ldy;
     int ntile, nslice, ntg;  // ntg = ceil(ntile / 4) tile groups (the four row tiles of a workgroup)
-    int units;               // ntg * nslice work units; workgroup w owns units [w*units/G, (w+1)*units/G)
+    int units;               // ntg * nslice work units, cut into one contiguous range per workgroup:
+    int unit_base, unit_rem; // units div / mod the number of workgroups (first_unit, owner_of_unit in bcq_device.h)
     unsigned tile_bytes;
     int scale_lane_mask;     // 63: one scale record per lane; 15: one per row (group = N)
 #ifdef BCQ_TRACE
@@ -576,13 +577,15 @@ __global__ __launch_bounds__(64 * NW) void bcq_skinny_kernel(SkinnyParams p)
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: tile pointers stay in SGPRs
     const int r = lane & 15, h = lane >> 4;
-    const int groups = gridDim.x;
 #ifdef BCQ_TRACE
     unsigned ts[kTraceSlots] = {};
     unsigned last = 0;
 #endif
     BCQ_SK_STAMP(0);  // wave started
-    const int u_begin = first_unit(blockIdx.x, p.units, groups), u_end = first_unit(blockIdx.x + 1, p.units, groups);
+    constexpr bool kFront = NW == 8;  // eight waves: one workgroup per compute unit (LDS, registers)
+    const int groups = gridDim.x;
+    const int u_begin = first_unit<kFront>(blockIdx.x, p.units, groups, p.unit_base, p.unit_rem);
+    const int u_end = first_unit<kFront>(blockIdx.x + 1, p.units, groups, p.unit_base, p.unit_rem);
     if (u_begin >= u_end) return;  // uniform for the workgroup, before any barrier
 
     int tg = u_begin / p.nslice, slice = u_begin - tg * p.nslice;
@@ -611,6 +614,11 @@ __global__ __launch_bounds__(64 * NW) void bcq_skinny_kernel(SkinnyParams p)
         const int seg_end = min(u_end, (tg + 1) * p.nslice);
         const int seg_tg = tg, seg_tile = tile;
         const bool seg_active = active;
+        // number of workgroups that contribute to this tile group; worked out here and parked in a vector register,
+        // because at the flush the kernels with four column groups have no scalar register to spare
+        int seg_arrivals = owner_of_unit<kFront>((tg + 1) * p.nslice - 1, p.units, groups, p.unit_base, p.unit_rem) -
+                           owner_of_unit<kFront>(tg * p.nslice, p.units, groups, p.unit_base, p.unit_rem) + 1;
+        asm volatile("" : "+v"(seg_arrivals));
         f32x4 acc[NB][2];
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) acc[nb][0] = acc[nb][1] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -676,8 +684,7 @@ __global__ __launch_bounds__(64 * NW) void bcq_skinny_kernel(SkinnyParams p)
         BCQ_SK_STAMP(2);  // (last) segment's units done
         // this workgroup is done with the tile group: flush (the next segment's first loads are in flight)
         if (seg_active) {
-            const int arrivals = owner_of_unit((seg_tg + 1) * p.nslice - 1, p.units, groups) -
-                                 owner_of_unit(seg_tg * p.nslice, p.units, groups) + 1;
+            const int arrivals = __builtin_amdgcn_readfirstlane(seg_arrivals);
             // (the lane index is passed through an empty asm so that the per-lane address arithmetic of
             // the flush is not hoisted out of this loop into registers that stay live during the units)
             int flush_lane = lane;
@@ -742,6 +749,8 @@ static hipError_t launch_skinny_one(SkinnyParams p, int parts, bool single_slice
     if (groups > p.units) groups = p.units;
     if (single_slice) groups = p.ntg;  // no workspace: one unit per tile group, nothing to combine
     if (groups < 1) groups = 1;
+    p.unit_base = (int)(p.units / groups);
+    p.unit_rem = (int)(p.units % groups);
     hipLaunchKernelGGL((bcq_skinny_kernel<Q, Z, SUB, VER, LDS_STEPS, NB, NW>), dim3((unsigned)groups), dim3(64 * NW), 0,
                        stream, p);
     return hipGetLastError();
@@ -807,7 +816,7 @@ hipError_t launch_skinny(const Geom &g, const void *packed, const uint16_t *X, i
     SkinnyParams p;
     p.blob = static_cast<const uint8_t *>(packed);
     p.M = g.M; p.N = g.N; p.Mp = g.Mp; p.ldx = ldx; p.ldy = ldy;
-    p.ntile = g.ntile; p.nslice = g.nslice; p.ntg = 0; p.units = 0;  // set per kernel (waves per workgroup)
+    p.ntile = g.ntile; p.nslice = g.nslice; p.ntg = 0; p.units = 0; p.unit_base = 0; p.unit_rem = 0;  // set per kernel (waves per workgroup)
     p.tile_bytes = g.tile_bytes;
     p.scale_lane_mask = g.scale_lanes - 1;
 #ifdef BCQ_TRACE
