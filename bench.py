@@ -250,7 +250,7 @@ def main():
                     frac=round(tfl / MFMA_PEAK_TFLOPS, 4), time_at_peak_us=round(t_mfma_us, 2))
         binding, other = (hbm, mfma) if t_hbm_us >= t_mfma_us else (mfma, hbm)
         roofline = dict(binding)
-        roofline.update(kernel="bcq_skinny_kernel (q=%d, %s, %s, batch %d) on %dx%d"
+        roofline.update(kernel="bcq_gemm_skinny's kernel for the shape (q=%d, %s, %s, batch %d) on %dx%d"
                                % (Q, "offset" if args.offset else "no offset",
                                   "row-wise scales" if args.rowwise else "group 128", B, dom["M"], dom["N"]),
                         bytes_per_launch=dom["weight_bytes"], flop_per_launch=flop, us_per_launch=us, traffic=None,

@@ -274,7 +274,9 @@ bcq_status bcq_read_probe(const void *buf, size_t bytes, void *sink, void *strea
  * that folds alpha into the matrix-core operand, 2 = the kernel that takes +-1
  * operands from an LDS table, with q = 4 at most 32 columns per pass; groups of
  * 32/64 always use 1; 3 = for batch 2..4 the kernel with sign-sum tables of four
- * vectors wherever it applies, 4 = never that one), "skinny_lds_steps" (3 or 4, kernel 2 only); 0 =
+ * vectors wherever it applies, 4 = never that one; 5 = for batch 2 the GEMV's table kernel
+ * with two vectors per table entry wherever it applies, 6 = never that one, the others chosen
+ * automatically), "skinny_lds_steps" (3 or 4, kernel 2 only); 0 =
  * automatic.
  * Unknown names or values return BCQ_ERR_INVALID_ARG.
  */

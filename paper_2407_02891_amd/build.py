@@ -27,7 +27,7 @@ def sources():
 def build_trace(verbose=False):
     """libbcq_trace.so: the GEMV compiled with per-wave time stamps (-DBCQ_TRACE), for trace_gemv.py."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    srcs = [os.path.join(CSRC, f) for f in ("bcq_gemv.hip", "bcq_skinny.hip", "bcq_lut4.hip", "bcq_pack.hip", "bcq_trace_api.hip")]
+    srcs = [os.path.join(CSRC, f) for f in ("bcq_gemv.hip", "bcq_gemv2.hip", "bcq_skinny.hip", "bcq_lut4.hip", "bcq_pack.hip", "bcq_trace_api.hip")]
     cmd = [hipcc] + HIPCC_FLAGS + ["-DBCQ_TRACE"] + srcs + ["-o", TRACE_LIB]
     if verbose:
         print(" ".join(cmd))

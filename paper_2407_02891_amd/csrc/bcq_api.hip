@@ -285,7 +285,7 @@ bcq_status bcq_set_option(const char *name, int32_t value)
         g_tuning.skinny_parts = value;
         return BCQ_OK;
     }
-    if (strcmp(name, "skinny_version") == 0 && value <= 4) {
+    if (strcmp(name, "skinny_version") == 0 && value <= 6) {
         g_tuning.skinny_version = value;
         return BCQ_OK;
     }

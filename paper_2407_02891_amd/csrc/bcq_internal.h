@@ -43,7 +43,8 @@ struct GemvTuning {
     int trace_groups = 0;   // tracing build, skinny kernel: workgroups that buffer has room for (8 waves each)
     int skinny_parts = 0;  // K split of the skinny kernel
     int skinny_version = 0;    // 1 = the first skinny kernel (alpha folded into A) also where the second applies,
-                               // 3 = the table kernel for up to four vectors where it applies, 4 = never that one
+                               // 3 = the table kernel for up to four vectors where it applies, 4 = never that one,
+                               // 5 = the two-vector table kernel where it applies, 6 = never that one
     int skinny_lds_steps = 0;  // second skinny kernel: MFMA steps per block whose A operand comes from the
                                // LDS table, 3 or 4 (0 = automatic = 4)
 };
@@ -56,6 +57,10 @@ hipError_t launch_skinny(const Geom &g, const void *packed, const uint16_t *X, i
 bool lut4_applies(const Geom &g, int batch, const void *workspace);
 hipError_t launch_lut4(const Geom &g, const void *packed, const uint16_t *X, int ldx, uint16_t *Y, int ldy, int batch,
                        void *workspace, const GemvTuning &tuning, hipStream_t stream);
+// The GEMV's tables with both vectors of a two-vector call side by side (bcq_gemv2.hip): batch == 2.
+bool gemv2_applies(const Geom &g, int batch, const void *workspace);
+hipError_t launch_gemv2(const Geom &g, const void *packed, const uint16_t *X, int ldx, uint16_t *Y, int ldy,
+                        void *workspace, const GemvTuning &tuning, hipStream_t stream);
 hipError_t launch_read_probe(const void *buf, size_t bytes, void *sink, hipStream_t stream);
 
 // Rows the file-scope split-K scratch array covers (bcq_gemv_noalloc): 1 MiB per GPU.

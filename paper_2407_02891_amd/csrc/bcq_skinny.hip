@@ -809,9 +809,18 @@ hipError_t launch_skinny(const Geom &g, const void *packed, const uint16_t *X, i
     // four only on the largest layers; it loses on smaller ones (9216 x 9216: 21.3 / 24.1 against 18.3 / 18.2) and
     // with one or two planes (its table builds and barriers do not shrink with q).
     const long long all_tiles = (long long)g.ntile * g.nslice;
+    // Two vectors: the GEMV's decomposition with both vectors' sign sums in one table entry (bcq_gemv2.hip).  Measured
+    // against the best of the kernels below, q = 3: 7168 x 28672 25.4 against 31.9 us, 28672 x 7168 23.7 / 31.2,
+    // 9216 x 36864 38.3 / 46.9, 9216 x 9216 13.2 / 17.2, 7168 x 7168 11.3 / 13.1 (q = 2, 7168 x 28672: 18.8 / 23.1); it
+    // loses where a compute unit gets less than a round of tiles (4096 x 4096 9.7 / 8.9, 1024 x 8192 9.3 / 7.9).
+    if (gemv2_applies(g, batch, workspace) &&
+        (tuning.skinny_version == 5 || (tuning.skinny_version == 0 && all_tiles >= 2048)))
+        return launch_gemv2(g, packed, X, ldx, Y, ldy, workspace, tuning, stream);
+    // (versions 5 and 6 only switch the two-vector kernel on and off: automatic choice among the others)
+    const int version = tuning.skinny_version >= 5 ? 0 : tuning.skinny_version;
     if (lut4_applies(g, batch, workspace) &&
-        (tuning.skinny_version == 3 ||
-         (tuning.skinny_version == 0 && g.q >= 3 && all_tiles >= (batch == 2 ? 12288 : 18432))))
+        (version == 3 ||
+         (version == 0 && g.q >= 3 && all_tiles >= (batch == 2 ? 12288 : 18432))))
         return launch_lut4(g, packed, X, ldx, Y, ldy, batch, workspace, tuning, stream);
     SkinnyParams p;
     p.blob = static_cast<const uint8_t *>(packed);
@@ -826,7 +835,7 @@ hipError_t launch_skinny(const Geom &g, const void *packed, const uint16_t *X, i
     // forced grid sizes (tuning runs, tests): a K split per tile group, or a plain number of workgroups
     const int parts = tuning.skinny_parts > 0 ? tuning.skinny_parts : -tuning.workgroups;
     const bool single = workspace == nullptr;  // only reachable for a single column slice
-    const int sub = g.sub, ver = tuning.skinny_version, steps = tuning.skinny_lds_steps;
+    const int sub = g.sub, ver = version, steps = tuning.skinny_lds_steps;
     // Up to 64 batch columns in one pass over the weights (the expanded operands are shared by the
     // groups of 16 columns); with several scaling groups per block one pass per 16 columns.
     const bool wide_ok = sub == 1;

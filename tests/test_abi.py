@@ -221,7 +221,7 @@ def test_misc_argument_checks():
     assert L.bcq_set_option(b"no_such_option", 1) == B.BCQ_ERR_INVALID_ARG
     assert L.bcq_set_option(b"workgroups", -1) == B.BCQ_ERR_INVALID_ARG
     assert L.bcq_set_option(b"workgroups", 0) == B.BCQ_OK
-    assert L.bcq_set_option(b"skinny_version", 5) == B.BCQ_ERR_INVALID_ARG
+    assert L.bcq_set_option(b"skinny_version", 7) == B.BCQ_ERR_INVALID_ARG
     assert L.bcq_set_option(b"skinny_lds_steps", 2) == B.BCQ_ERR_INVALID_ARG
     for name, ok_value in ((b"skinny_version", 1), (b"skinny_lds_steps", 3), (b"waves", 8), (b"skinny_parts", 5)):
         assert L.bcq_set_option(name, ok_value) == B.BCQ_OK

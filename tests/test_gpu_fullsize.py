@@ -58,11 +58,13 @@ def test_llama70b_shapes(M, N, q):
                                                   (36864, 9216, 3, False, 4), (36864, 9216, 3, False, 16),
                                                   (9216, 36864, 3, False, 4), (9216, 36864, 3, False, 16),
                                                   (7168, 28672, 3, False, 64),
-                                                  (7168, 28672, 3, False, 32), (7168, 7168, 2, True, 24)])
+                                                  (7168, 28672, 3, False, 32), (7168, 7168, 2, True, 24),
+                                                  (7168, 28672, 3, False, 2), (9216, 36864, 3, True, 2)])
 def test_skinny_fullsize(M, N, q, offset, batch):
     """configs[2] (q=2 with offset, batch 8, all three layers), configs[3] (batch 4 and 16, outlier channels,
-    all three layers), the dominant layer of configs[1] at the widest batch of one pass (64), and 17..32 columns
-    (the table kernel with two column groups, which large layers use)"""
+    all three layers), the dominant layer of configs[1] at the widest batch of one pass (64), 17..32 columns
+    (the table kernel with two column groups, which large layers use), and two vectors (the two-vector table
+    kernel, in the launch shape large layers get)"""
     _check(M, N, q, offset, batch=batch, outlier_frac=0.01 if 9216 in (M, N) else 0.0)
 
 

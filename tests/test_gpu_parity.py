@@ -409,6 +409,54 @@ def test_table_kernel_for_up_to_four_vectors(workgroups, batch):
         bcq.set_option("skinny_version", 0)
 
 
+@pytest.mark.parametrize("workgroups", [0, 1, 3, 7, 50])
+def test_two_vector_table_kernel(workgroups):
+    """Two activation vectors on layers from 2048 tiles on: the GEMV's decomposition with both vectors' sign sums
+    in one table entry (bcq_gemv2.hip).  Forced here on small shapes: ragged rows and columns, a single column
+    slice (no split-K), fewer tiles than waves, one to four planes with and without offset, row-wise scales and
+    groups of 256, any grid size; bit for bit the oracle's result (one binary16 rounding) on exact inputs, twice in
+    a row, workspace left zero; gate on random inputs with outlier channels; padded rows of X and Y; binary16
+    subnormal scales."""
+    try:
+        bcq.set_option("skinny_version", 5)
+        bcq.set_option("workgroups", workgroups)
+        for (M, N, q, off, group) in [(96, 2048, 3, False, 128), (300, 5120, 3, True, 128), (70, 1536, 2, True, 128),
+                                      (1000, 2560, 1, False, 128), (203, 3200, 4, True, 128), (96, 2048, 3, True, 2048),
+                                      (40, 1024, 3, False, 128), (520, 512, 2, True, 128), (777, 6656, 3, False, 256),
+                                      (33, 640, 4, False, 128)]:
+            L = bcq_synth.make_exact_layer(M, N, q, group=group, offset=off, batch=2, seed=M + q)
+            pl = U.upload_and_pack(L, max_batch=2)
+            expect = ref.gemm(L.planes, L.alpha, L.offset, L.x).astype(np.float16).astype(np.float64)
+            for _ in range(2):
+                assert np.array_equal(U.gpu_gemm(pl, U.x_dev(L)).astype(np.float64), expect), (M, N, q, off, group)
+            assert pl.workspace is None or not pl.workspace.cpu().numpy().any()
+        _run_case(600, 4608, 3, 128, True, batch=2, seed=workgroups, outlier_frac=0.01)
+        _run_case(1024, 4096, 2, 128, False, batch=2, seed=workgroups + 1)
+        L = bcq_synth.make_exact_layer(150, 3072, 3, group=128, offset=True, batch=2, seed=77)
+        pl = U.upload_and_pack(L, max_batch=2)
+        expect = ref.gemm(L.planes, L.alpha, L.offset, L.x).astype(np.float16).astype(np.float64)
+        X = torch.zeros((2, L.N + 64), dtype=torch.float16, device="cuda")
+        X[:, :L.N] = U.x_dev(L)
+        Y = torch.full((2, L.M + 10), 3.0, dtype=torch.float16, device="cuda")
+        bcq.gemm_skinny(pl.desc, pl.packed, X, X.stride(0), Y, Y.stride(0), 2, pl.workspace)
+        torch.cuda.synchronize()
+        assert np.array_equal(Y[:, :L.M].cpu().numpy().astype(np.float64), expect)
+        assert torch.all(Y[:, L.M:] == 3.0)
+        # every alpha and offset a binary16 subnormal: exact in binary32, so bit for bit the oracle's rounded result
+        L = bcq_synth.make_exact_layer(150, 2048, 3, group=128, offset=True, batch=2, seed=92)
+        rng = np.random.default_rng(7)
+        L.alpha = rng.integers(1, 1024, size=L.alpha.shape, dtype=np.uint16).view(np.float16)
+        z = rng.integers(1, 1024, size=L.offset.shape, dtype=np.uint16) | (rng.integers(0, 2, size=L.offset.shape, dtype=np.uint16) << 15)
+        L.offset = z.view(np.float16)
+        y_ref = ref.gemm(L.planes, L.alpha, L.offset, L.x)
+        assert np.abs(y_ref).max() > 2.0 ** -12, "the scales must matter"
+        pl = U.upload_and_pack(L, max_batch=2)
+        assert np.array_equal(U.gpu_gemm(pl, U.x_dev(L)).astype(np.float64), y_ref.astype(np.float16).astype(np.float64))
+    finally:
+        bcq.set_option("workgroups", 0)
+        bcq.set_option("skinny_version", 0)
+
+
 @pytest.mark.parametrize("workgroups", [1, 4, 7, 11, 29])
 @pytest.mark.parametrize("version", [1, 2])
 def test_skinny_work_split_does_not_change_results(workgroups, version):
