@@ -612,7 +612,7 @@ __global__ __launch_bounds__(64 * NW) void bcq_skinny_kernel(SkinnyParams p)
     while (u < u_end) {
         // one segment: the units of this workgroup that belong to tile group `tg`
         const int seg_end = min(u_end, (tg + 1) * p.nslice);
-        const int seg_tg = tg, seg_tile = tile;
+        const int seg_tile = tile;
         const bool seg_active = active;
         // number of workgroups that contribute to this tile group; worked out here and parked in a vector register,
         // because at the flush the kernels with four column groups have no scalar register to spare
