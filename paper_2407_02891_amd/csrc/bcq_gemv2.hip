@@ -160,28 +160,26 @@ __global__ __launch_bounds__(kGemv2Waves * 64) void bcq_gemv2_kernel(Gemv2Params
     // waits for its tile (and with it for the atomics issued one iteration earlier), completes the rows of tile
     // k-2, issues the atomics of tile k-1, requests tile k+1 and computes tile k ----
     const bool split_k = p.nslice > 1;
-    const bool reporter = (lane & 16) == 0;                // lanes 0..15 and 32..47
-    const int rep_row = (lane & 15) | ((lane >> 5) << 4);  // their row inside the tile
+    // After the lane swaps the sums of rows 0..15 sit in the lanes 0..15 AND 16..31, those of rows 16..31 in the lanes
+    // 32..47 AND 48..63.  The first copy reports vector 0, the second vector 1: one atomic (or store) instruction of 64
+    // lanes per tile instead of two of 32.
+    const int vec = (lane >> 4) & 1;                       // the vector this lane reports
+    const int rep_row = (lane & 15) | ((lane >> 5) << 4);  // its row inside the tile
+    unsigned long long *const accum = p.accum + (size_t)vec * p.Mp;
     int held_tile = -1;
-    f32x2 held = {0.0f, 0.0f};
+    float held = 0.0f;
     int pend_tile = -1;
-    unsigned long long pend_old[2] = {0, 0}, pend_mine[2] = {0, 0};
+    unsigned long long pend_old = 0, pend_mine = 0;
 
     for (int tile = t_begin; tile < t_end; tile += NW) {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        if (split_k && reporter) {
-            if (pend_tile >= 0) {
-#pragma unroll
-                for (int v = 0; v < 2; ++v) complete_row2(p, v, pend_tile * kTileRows + rep_row, pend_old[v] + pend_mine[v]);
-            }
+        if (split_k) {
+            if (pend_tile >= 0) complete_row2(p, vec, pend_tile * kTileRows + rep_row, pend_old + pend_mine);
             pend_tile = held_tile;
             if (held_tile >= 0) {
-#pragma unroll
-                for (int v = 0; v < 2; ++v) {
-                    pend_mine[v] = encode_partial_f32(held[v]);
-                    pend_old[v] = __hip_atomic_fetch_add(p.accum + (size_t)v * p.Mp + held_tile * kTileRows + rep_row,
-                                                         pend_mine[v], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                }
+                pend_mine = encode_partial_f32(held);
+                pend_old = __hip_atomic_fetch_add(accum + held_tile * kTileRows + rep_row, pend_mine, __ATOMIC_RELAXED,
+                                                  __HIP_MEMORY_SCOPE_AGENT);
             }
         }
         TileRegs<Q, Z, 1> nxt;
@@ -206,38 +204,27 @@ __global__ __launch_bounds__(kGemv2Waves * 64) void bcq_gemv2_kernel(Gemv2Params
             }
             acc[t] = a;
         }
-        // the four block owners of each row summed: rows 0..15 end up in lanes 0..15, rows 16..31 in lanes 32..47
-        const f32x2 out = {sum_block_owners(acc[0][0], acc[1][0]), sum_block_owners(acc[0][1], acc[1][1])};
+        const float out0 = sum_block_owners(acc[0][0], acc[1][0]), out1 = sum_block_owners(acc[0][1], acc[1][1]);
+        const float out = vec ? out1 : out0;
         if (split_k) {
             held = out;
             held_tile = tile;
         } else {
             const int row = tile * kTileRows + rep_row;
-            if (reporter && row < p.M) {
-                p.Y[row] = float_to_half_bits(out[0]);
-                p.Y[(size_t)p.ldy + row] = float_to_half_bits(out[1]);
-            }
+            if (row < p.M) p.Y[(size_t)vec * p.ldy + row] = float_to_half_bits(out);
         }
         if (tile + NW < t_end) cur = nxt;
     }
 
-    if (split_k && reporter) {  // drain: two tiles may still be in the pipeline
+    if (split_k) {  // drain: two tiles may still be in the pipeline
         if (held_tile >= 0) {
-            unsigned long long mine[2], old[2];
-#pragma unroll
-            for (int v = 0; v < 2; ++v) {
-                mine[v] = encode_partial_f32(held[v]);
-                old[v] = __hip_atomic_fetch_add(p.accum + (size_t)v * p.Mp + held_tile * kTileRows + rep_row, mine[v],
-                                                __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
-#pragma unroll
-            for (int v = 0; v < 2; ++v) {
-                if (pend_tile >= 0) complete_row2(p, v, pend_tile * kTileRows + rep_row, pend_old[v] + pend_mine[v]);
-                complete_row2(p, v, held_tile * kTileRows + rep_row, old[v] + mine[v]);
-            }
+            const unsigned long long mine = encode_partial_f32(held);
+            const unsigned long long old = __hip_atomic_fetch_add(accum + held_tile * kTileRows + rep_row, mine,
+                                                                  __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (pend_tile >= 0) complete_row2(p, vec, pend_tile * kTileRows + rep_row, pend_old + pend_mine);
+            complete_row2(p, vec, held_tile * kTileRows + rep_row, old + mine);
         } else if (pend_tile >= 0) {
-#pragma unroll
-            for (int v = 0; v < 2; ++v) complete_row2(p, v, pend_tile * kTileRows + rep_row, pend_old[v] + pend_mine[v]);
+            complete_row2(p, vec, pend_tile * kTileRows + rep_row, pend_old + pend_mine);
         }
     }
 }
