@@ -810,9 +810,9 @@ hipError_t launch_skinny(const Geom &g, const void *packed, const uint16_t *X, i
     // with one or two planes (its table builds and barriers do not shrink with q).
     const long long all_tiles = (long long)g.ntile * g.nslice;
     // Two vectors: the GEMV's decomposition with both vectors' sign sums in one table entry (bcq_gemv2.hip).  Measured
-    // against the best of the kernels below, q = 3: 7168 x 28672 25.4 against 31.9 us, 28672 x 7168 23.7 / 31.2,
-    // 9216 x 36864 38.3 / 46.9, 9216 x 9216 13.2 / 17.2, 7168 x 7168 11.3 / 13.1 (q = 2, 7168 x 28672: 18.8 / 23.1); it
-    // loses where a compute unit gets less than a round of tiles (4096 x 4096 9.7 / 8.9, 1024 x 8192 9.3 / 7.9).
+    // against the best of the kernels below, q = 3: 7168 x 28672 23.6 against 32.4 us, 28672 x 7168 22.5 / 32.1,
+    // 9216 x 36864 36.3 / 49.4, 9216 x 9216 12.7 / 17.4, 7168 x 7168 10.7 / 13.1 (q = 2, 7168 x 28672: 18.0 / 22.8); it
+    // loses where a compute unit gets less than a round of tiles (4096 x 4096 9.1 / 8.6, 1024 x 8192 8.8 / 7.9).
     if (gemv2_applies(g, batch, workspace) &&
         (tuning.skinny_version == 5 || (tuning.skinny_version == 0 && all_tiles >= 2048)))
         return launch_gemv2(g, packed, X, ldx, Y, ldy, workspace, tuning, stream);
